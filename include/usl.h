@@ -1,0 +1,140 @@
+/*
+ * usl -- training hot path of the uniformly-sparse extreme-classification output layer
+ * (every one of m labels has exactly k incoming weights from a layer of width d), as
+ * hand-written HIP kernels for gfx950 behind a plain C ABI.
+ *
+ * Method: Schultheis & Babbar, "Towards Memory-Efficient Training for Extremely Large
+ * Output Spaces -- Learning with 500k Labels on a Single Commodity GPU" (arXiv 2306.03725).
+ * Sections cited below are the paper's.
+ *
+ * LAYOUT (all row-major, all DEVICE memory owned by the caller unless marked "host"):
+ *   idx    [m][k]  int32    feature that feeds slot t of label j, 0-based, values in [0, d),
+ *                           pairwise distinct within a row.  This is the transpose of the
+ *                           paper's indices[s][m] (Section 3.2, Figure 1c); k is the paper's s.
+ *   W      [m][k]  float32, or bfloat16 when the context was created with USL_BF16
+ *   m1, m2 [m][k]  float32  Adam moments
+ *   grad_W [m][k]  float32
+ *   x      [b][d]  float32 / bfloat16 (same storage type as W)   activations (paper: features)
+ *   grad_x [b][d]  float32
+ *   out, g [b][m]  float32  scores and upstream gradient (paper: output, backward)
+ *   targets        CSR: tgt_off[b+1] int64 (tgt_off[0] = 0), tgt_lab[tgt_off[b]] int32 label ids
+ *
+ * CALLS are asynchronous: they enqueue kernels on the context's stream and return.  The only
+ * calls that wait for the stream are those handed a non-NULL host out-pointer.
+ *
+ * ERRORS: every call returns a usl_status; nothing aborts or throws across this boundary.
+ * Preconditions that can be checked on the host (NULL pointers, batch outside [1, max_b],
+ * k > d, fraction outside [0,1], t < 1, ...) are checked before anything is launched, and a
+ * failed check launches nothing.  Index CONTENTS are the caller's responsibility on the hot
+ * path (usl_validate_indices checks them).  Target label ids must lie in [0, m).
+ * usl_last_error returns a context-owned message for the most recent failure.
+ *
+ * THREADS: a context is not thread-safe; use one context per host thread / stream.
+ */
+#ifndef USL_H
+#define USL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct usl_ctx usl_ctx; /* opaque: shape, storage type, stream, device scratch */
+
+typedef enum {
+    USL_OK = 0,
+    USL_EINVAL = 1,       /* NULL pointer or a scalar argument out of range */
+    USL_ESHAPE = 2,       /* sizes the library cannot take (k > d, b > max_b, m*k too large...) */
+    USL_ENOMEM = 3,       /* host or device allocation failed */
+    USL_EHIP = 4,         /* a HIP call failed (message in usl_last_error), or no GPU */
+    USL_EUNSUPPORTED = 5  /* a valid request this build has no kernel for */
+} usl_status;
+
+typedef enum { USL_F32 = 0, USL_BF16 = 1 } usl_dtype; /* storage of x and W; sums are float32 */
+
+/* Create a context for a layer of m labels, input width d, fan-in k, batches of at most
+ * max_b instances.  Limits: 1 <= k <= d <= 2^24, 1 <= m, m*k < 2^32, max_b >= 1.
+ * hip_stream is a hipStream_t (NULL = the null stream).  No device memory is touched until
+ * the first call that launches; a context can be created on a host without a GPU. */
+usl_status usl_create(usl_ctx** ctx, int64_t m, int32_t d, int32_t k, int32_t max_b,
+                      usl_dtype storage, void* hip_stream);
+usl_status usl_destroy(usl_ctx* ctx); /* frees the context and its device scratch; NULL is OK */
+usl_status usl_set_stream(usl_ctx* ctx, void* hip_stream);
+/* The library keeps a column-major copy of the connectivity for usl_backward_input, keyed by the
+ * idx pointer and rebuilt after usl_init_indices / usl_redistribute.  A caller that rewrites the
+ * contents of idx by any other means must call this before the next usl_backward_input. */
+usl_status usl_invalidate(usl_ctx* ctx);
+const char* usl_last_error(const usl_ctx* ctx); /* never NULL; owned by the context */
+const char* usl_version(void);
+
+/* Initial connectivity (Section 4.1: connections drawn uniformly at random, the same number
+ * for every label).  Fills idx[m][k] with k distinct columns per row: the refill rule of
+ * usl_redistribute applied to rows whose slots are all empty, with epoch = 2^64 - 1. */
+usl_status usl_init_indices(usl_ctx* ctx, int32_t* idx, uint64_t seed);
+
+/* Forward product (Section 3.2, Algorithm 1): out[i][j] = sum_t W[j][t] * x[i][idx[j][t]].
+ * x: [b][d] storage type; W: [m][k] storage type; out: [b][m] float32, overwritten. */
+usl_status usl_forward(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W,
+                       float* out, int32_t b);
+
+/* One-vs-all binary cross-entropy summed over all labels (Section 2, sum of a binary loss
+ * over labels; BCE is the comparison loss of Section 4.4), on sparse targets:
+ *   y[i][j] = 1 iff j is listed for instance i (a set: repeats count once)
+ *   loss = scale * sum_ij [ max(z,0) - z*y + log(1 + exp(-|z|)) ],  z = out[i][j]
+ *   g[i][j] = scale * (sigmoid(z) - y)
+ * g may be the same buffer as out.  loss: one float32 in device memory, overwritten. */
+usl_status usl_bce_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_off,
+                             const int32_t* tgt_lab, float scale, float* g, float* loss,
+                             int32_t b);
+
+/* Gradient of the connection values (Section 3.3, Algorithm 3):
+ * grad_W[j][t] = sum_i g[i][j] * x[i][idx[j][t]].  grad_W is overwritten. */
+usl_status usl_backward_weight(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx,
+                               float* grad_W, int32_t b);
+
+/* Gradient of the input features (Section 3.3, Algorithm 2):
+ * grad_x[i][c] = sum over connections (j,t) with idx[j][t] == c of W[j][t] * g[i][j].
+ * grad_x is overwritten (not accumulated into).  The order of the additions is not fixed. */
+usl_status usl_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx, const void* W,
+                              float* grad_x, int32_t b);
+
+/* Adam (the optimizer of Section 4.1; update rule of Kingma & Ba, Algorithm 1) on the m*k
+ * connection values, t = 1-based step number:
+ *   m1 <- beta1*m1 + (1-beta1)*gW;  m2 <- beta2*m2 + (1-beta2)*gW^2
+ *   W  <- W - lr * (m1/(1-beta1^t)) / (sqrt(m2/(1-beta2^t)) + eps)
+ * With USL_BF16 the new W is rounded to bfloat16 (nearest even); moments stay float32. */
+usl_status usl_adam_step(usl_ctx* ctx, void* W, const float* grad_W, float* m1, float* m2,
+                         int64_t t, float lr, float beta1, float beta2, float eps);
+
+/* Connection redistribution (Section 2: the prune / redistribute cycle of SET; Section 3.2:
+ * a column's slots never move).  In place:
+ *   1. n = floor(fraction * m*k) connections with the smallest magnitude in the whole layer are
+ *      removed; the order is (bit pattern of |W|, flat slot number j*k+t), so +0 and -0 tie,
+ *      NaN is never removed, and equal magnitudes go in slot order.
+ *   2. every removed slot, row by row and in increasing t, takes a new column drawn uniformly
+ *      from the features its row is not connected to (columns removed in step 1 are eligible
+ *      again): candidate number a = 0,1,2,... is word 0 of Philox-4x32-10 with counter
+ *      (j, t, a, epoch mod 2^32) and key (seed mod 2^32, (seed >> 32) xor (epoch >> 32)),
+ *      mapped to a column by (word * d) >> 32, and the first candidate that differs from every
+ *      occupied slot of the row is taken.
+ *   3. a new connection starts with W = +0 and m1 = m2 = 0.
+ * The result is a function of (idx, W, fraction, seed, epoch) only.  epoch 2^64-1 is reserved.
+ * n_rewired_host: optional host pointer that receives n (known before launch: no wait). */
+usl_status usl_redistribute(usl_ctx* ctx, int32_t* idx, void* W, float* m1, float* m2,
+                            double fraction, uint64_t seed, uint64_t epoch,
+                            int64_t* n_rewired_host);
+
+/* Debug check of the uniform-sparsity invariant (Section 3.2): counts rows of idx that hold a
+ * value outside [0, d) or the same column twice.  n_bad_host: host pointer; the call waits. */
+usl_status usl_validate_indices(usl_ctx* ctx, const int32_t* idx, int64_t* n_bad_host);
+
+/* Raw generator words for conformance tests: out[4*i .. 4*i+3] (device, uint32) receives
+ * Philox-4x32-10 of counter ctr[4*i .. 4*i+3] (device) under key (key0, key1), i < n. */
+usl_status usl_philox_words(usl_ctx* ctx, const uint32_t* ctr, uint32_t key0, uint32_t key1,
+                            uint32_t* out, int64_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* USL_H */

@@ -1,0 +1,539 @@
+// Forward product (Algorithm 1) and weight gradient (Algorithm 3) of the uniformly-sparse layer.
+//
+// Both walk the same gather: for a pair (instance i, label j) the k values x[i][idx[j][t]].
+// Design for gfx950: a workgroup owns a block of labels and keeps their k indices (packed two
+// per register) and k weights -- or k gradient accumulators -- in VGPRs for its whole life.
+// It then walks over the instances; each activation row (or a tile of rows when d is small,
+// or a slice of the row when it exceeds the LDS budget) is copied once into LDS with coalesced
+// 16-byte loads, and every gather is an LDS read.  idx and W therefore leave HBM once per
+// workgroup, x is re-read once per label block (it stays in L2 / Infinity Cache), and out /
+// grad_W are written with coalesced stores.
+#include "usl_internal.h"
+
+namespace {
+
+template <typename TS, int NT>
+__device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict__ lds, int n,
+                                      bool vec_ok) {
+    if (vec_ok) {
+        const uint4* s = reinterpret_cast<const uint4*>(src);
+        uint4* dd = reinterpret_cast<uint4*>(lds);
+        const int nv = (int)((size_t)n * sizeof(TS) / 16);
+        for (int v = threadIdx.x; v < nv; v += NT) dd[v] = s[v];
+    } else {
+        for (int c = threadIdx.x; c < n; c += NT) lds[c] = src[c];
+    }
+}
+
+__device__ __forceinline__ float lds_val(const float* row, uint32_t c) { return row[c]; }
+__device__ __forceinline__ float lds_val(const uint16_t* row, uint32_t c) {
+    return usl_bf16_to_f32(row[c]);
+}
+
+// Rows [row0, row0+NT) of a row-major [m][KW] matrix of 32-bit words (KW % 4 == 0, base 16-byte
+// aligned) are copied into LDS with coalesced 16-byte loads, one padding word per row, so that
+// afterwards lane r can read "its" row word by word without bank conflicts (stride KW+1).
+template <int KW, int NT>
+__device__ __forceinline__ void rows_to_lds(const uint32_t* __restrict__ src, int64_t row0,
+                                            int64_t m, uint32_t* __restrict__ lds) {
+    int64_t nvalid = m - row0;
+    nvalid = nvalid < 0 ? 0 : (nvalid > NT ? NT : nvalid);
+    const int nv = (int)(nvalid * KW / 4);
+    const uint4* s = reinterpret_cast<const uint4*>(src + row0 * KW);
+    for (int v = threadIdx.x; v < nv; v += NT) {
+        const uint4 q = s[v];
+        const int f = v * 4, r = f / KW, t = f % KW;
+        uint32_t* p = lds + r * (KW + 1) + t;
+        p[0] = q.x; p[1] = q.y; p[2] = q.z; p[3] = q.w;
+    }
+}
+// The reverse: every lane has put its KW words at lds[lane*(KW+1) ..]; rows leave with coalesced
+// 16-byte stores, or float atomic adds when several workgroups share the destination.
+template <int KW, int NT, bool ATOMIC>
+__device__ __forceinline__ void lds_to_rows(const uint32_t* __restrict__ lds, float* __restrict__ dst,
+                                            int64_t row0, int64_t m) {
+    int64_t nvalid = m - row0;
+    nvalid = nvalid < 0 ? 0 : (nvalid > NT ? NT : nvalid);
+    const int nv = (int)(nvalid * KW / 4);
+    float* base = dst + row0 * KW;
+    for (int v = threadIdx.x; v < nv; v += NT) {
+        const int f = v * 4, r = f / KW, t = f % KW;
+        const uint32_t* p = lds + r * (KW + 1) + t;
+        const float4 q = make_float4(__uint_as_float(p[0]), __uint_as_float(p[1]),
+                                     __uint_as_float(p[2]), __uint_as_float(p[3]));
+        if (ATOMIC) {
+            unsafeAtomicAdd(base + f, q.x); unsafeAtomicAdd(base + f + 1, q.y);
+            unsafeAtomicAdd(base + f + 2, q.z); unsafeAtomicAdd(base + f + 3, q.w);
+        } else {
+            reinterpret_cast<float4*>(base)[v] = q;
+        }
+    }
+}
+
+// Brings the k indices of NT consecutive labels into registers, two 16-bit indices per register.
+template <int K, int NT>
+__device__ __forceinline__ void fetch_idx_packed(const int32_t* __restrict__ idx, int64_t row0,
+                                                 int64_t m, uint32_t* lds, uint32_t (&pk)[K / 2]) {
+    __syncthreads();
+    rows_to_lds<K, NT>(reinterpret_cast<const uint32_t*>(idx), row0, m, lds);
+    __syncthreads();
+    const bool valid = row0 + threadIdx.x < m;
+    const uint32_t* p = lds + threadIdx.x * (K + 1);
+#pragma unroll
+    for (int q = 0; q < K / 2; ++q) pk[q] = valid ? (p[2 * q] | (p[2 * q + 1] << 16)) : 0u;
+}
+template <int K>
+__device__ __forceinline__ uint32_t col_of(const uint32_t (&pk)[K / 2], int t) {
+    return (t & 1) ? (pk[t >> 1] >> 16) : (pk[t >> 1] & 0xFFFFu);
+}
+
+template <int K, int NT>
+__device__ __forceinline__ void fetch_w(const float* __restrict__ W, int64_t row0, int64_t m,
+                                        uint32_t* lds, float (&w)[K]) {
+    __syncthreads();
+    rows_to_lds<K, NT>(reinterpret_cast<const uint32_t*>(W), row0, m, lds);
+    __syncthreads();
+    const bool valid = row0 + threadIdx.x < m;
+    const uint32_t* p = lds + threadIdx.x * (K + 1);
+#pragma unroll
+    for (int t = 0; t < K; ++t) w[t] = valid ? __uint_as_float(p[t]) : 0.f;
+}
+template <int K, int NT>
+__device__ __forceinline__ void fetch_w(const uint16_t* __restrict__ W, int64_t row0, int64_t m,
+                                        uint32_t* lds, float (&w)[K]) {
+    __syncthreads();
+    rows_to_lds<K / 2, NT>(reinterpret_cast<const uint32_t*>(W), row0, m, lds);
+    __syncthreads();
+    const bool valid = row0 + threadIdx.x < m;
+    const uint32_t* p = lds + threadIdx.x * (K / 2 + 1);
+#pragma unroll
+    for (int q = 0; q < K / 2; ++q) {
+        const uint32_t u = valid ? p[q] : 0u;
+        w[2 * q] = __uint_as_float(u << 16);
+        w[2 * q + 1] = __uint_as_float(u & 0xFFFF0000u);
+    }
+}
+
+// Stops the compiler from hoisting the unpacked indices out of the instance loop: unpacking is two
+// cheap VALU operations per gather, holding all k unpacked indices would double the register need.
+template <int N>
+__device__ __forceinline__ void keep_packed(uint32_t (&pk)[N]) {
+#pragma unroll
+    for (int q = 0; q < N; ++q) asm volatile("" : "+v"(pk[q]));
+}
+
+struct TileGeom {
+    int rows_per_tile;  // activation rows staged together (1 when the row is sliced)
+    int part_cols;      // columns per slice
+    int nparts;         // slices per row
+    int inst_per_group; // instances handled by one blockIdx.y
+    int vec_ok;         // 16-byte copies allowed
+};
+
+// ---------------------------------------------------------------------------- forward
+// MODE 0: a whole activation row fits LDS, one row per stage.
+// MODE 1: the row is cut into slices of part_cols columns; gathers outside the slice are masked.
+// MODE 2: small rows, rows_per_tile of them per stage (used with one label per lane).
+template <int K, int LPT, int NT, typename TS, int MODE>
+__global__ void __launch_bounds__(NT)
+k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* __restrict__ W,
+          float* __restrict__ out, int64_t m, int d, int b, TileGeom tg) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    TS* lds = reinterpret_cast<TS*>(lds_raw);
+    const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
+    uint32_t pk[LPT][K / 2];
+    float w[LPT][K];
+#pragma unroll
+    for (int l = 0; l < LPT; ++l) {
+        const int64_t row0 = j0 + (int64_t)l * NT;
+        fetch_idx_packed<K, NT>(idx, row0, m, reinterpret_cast<uint32_t*>(lds_raw), pk[l]);
+        fetch_w<K, NT>(W, row0, m, reinterpret_cast<uint32_t*>(lds_raw), w[l]);
+    }
+    const int64_t jme = j0 + threadIdx.x;  // label of slot l is jme + l*NT
+    const int i_begin = blockIdx.y * tg.inst_per_group;
+    const int i_end = min(b, i_begin + tg.inst_per_group);
+    if (MODE == 2) {
+        for (int it = i_begin; it < i_end; it += tg.rows_per_tile) {
+            const int rows = min(tg.rows_per_tile, i_end - it);
+            __syncthreads();
+            stage<TS, NT>(x + (size_t)it * d, lds, rows * d, tg.vec_ok);
+            __syncthreads();
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                const TS* row = lds + (size_t)r * d;
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) {
+                    float acc = 0.f;
+                    keep_packed(pk[l]);
+#pragma unroll
+                    for (int t = 0; t < K; ++t)
+                        acc = fmaf(w[l][t], lds_val(row, col_of<K>(pk[l], t)), acc);
+                    if (jme + (int64_t)l * NT < m) out[(size_t)(it + r) * m + jme + (int64_t)l * NT] = acc;
+                }
+            }
+        }
+    } else {
+#pragma unroll 1
+        for (int i = i_begin; i < i_end; ++i) {
+            float acc[LPT];
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) acc[l] = 0.f;
+            const int nparts = MODE == 1 ? tg.nparts : 1;
+#pragma unroll 1
+            for (int part = 0; part < nparts; ++part) {
+                const int c0 = part * tg.part_cols;
+                const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
+                __syncthreads();
+                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+                __syncthreads();
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) {
+                    keep_packed(pk[l]);
+#pragma unroll
+                    for (int t = 0; t < K; ++t) {
+                        const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
+                        if (MODE == 0 || c < cols) acc[l] = fmaf(w[l][t], lds_val(lds, c), acc[l]);
+                        // a few gathers in flight at a time: their results would otherwise
+                        // crowd out the resident indices and weights
+                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                    }
+                    // finish the sum here; left alone the compiler sinks the multiply-adds into
+                    // the guarded store below and keeps every gathered value alive until then
+                    asm volatile("" : "+v"(acc[l]));
+                }
+            }
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+                if (jme + (int64_t)l * NT < m) out[(size_t)i * m + jme + (int64_t)l * NT] = acc[l];
+        }
+    }
+}
+
+// any k, any d: one thread per label, idx / W re-read from global memory for every instance
+template <int NT, typename TS>
+__global__ void __launch_bounds__(NT)
+k_forward_generic(const TS* __restrict__ x, const int32_t* __restrict__ idx,
+                  const TS* __restrict__ W, float* __restrict__ out, int64_t m, int d, int k, int b,
+                  TileGeom tg) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    TS* lds = reinterpret_cast<TS*>(lds_raw);
+    const int64_t j = (int64_t)blockIdx.x * NT + threadIdx.x;
+    const int64_t jj = j < m ? j : m - 1;
+    const int i_begin = blockIdx.y * tg.inst_per_group;
+    const int i_end = min(b, i_begin + tg.inst_per_group);
+    for (int i = i_begin; i < i_end; ++i) {
+        float acc = 0.f;
+        for (int part = 0; part < tg.nparts; ++part) {
+            const int c0 = part * tg.part_cols;
+            const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
+            __syncthreads();
+            stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+            __syncthreads();
+            for (int t = 0; t < k; ++t) {
+                const uint32_t c = (uint32_t)idx[jj * k + t] - (uint32_t)c0;
+                if (c < cols) acc = fmaf(usl_load_f32<TS>(W, (size_t)(jj * k + t)), lds_val(lds, c), acc);
+            }
+        }
+        if (j < m) out[(size_t)i * m + j] = acc;
+    }
+}
+
+// ---------------------------------------------------------------------------- weight gradient
+template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC>
+__global__ void __launch_bounds__(NT)
+k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
+                  const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m, int d,
+                  int b, TileGeom tg) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    TS* lds = reinterpret_cast<TS*>(lds_raw);
+    const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
+    uint32_t pk[LPT][K / 2];
+    float acc[LPT][K];
+#pragma unroll
+    for (int l = 0; l < LPT; ++l) {
+        fetch_idx_packed<K, NT>(idx, j0 + (int64_t)l * NT, m, reinterpret_cast<uint32_t*>(lds_raw), pk[l]);
+#pragma unroll
+        for (int t = 0; t < K; ++t) acc[l][t] = 0.f;
+    }
+    const int64_t jme = j0 + threadIdx.x;
+    const int i_begin = blockIdx.y * tg.inst_per_group;
+    const int i_end = min(b, i_begin + tg.inst_per_group);
+    if (MODE == 2) {
+        for (int it = i_begin; it < i_end; it += tg.rows_per_tile) {
+            const int rows = min(tg.rows_per_tile, i_end - it);
+            __syncthreads();
+            stage<TS, NT>(x + (size_t)it * d, lds, rows * d, tg.vec_ok);
+            __syncthreads();
+#pragma unroll 1
+            for (int r = 0; r < rows; ++r) {
+                const TS* row = lds + (size_t)r * d;
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) {
+                    const int64_t j = jme + (int64_t)l * NT;
+                    const float gv = j < m ? g[(size_t)(it + r) * m + j] : 0.f;
+                    keep_packed(pk[l]);
+#pragma unroll
+                    for (int t = 0; t < K; ++t)
+                        acc[l][t] = fmaf(gv, lds_val(row, col_of<K>(pk[l], t)), acc[l][t]);
+                }
+            }
+        }
+    } else {
+#pragma unroll 1
+        for (int i = i_begin; i < i_end; ++i) {
+            float gv[LPT];
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) {
+                const int64_t j = jme + (int64_t)l * NT;
+                gv[l] = j < m ? g[(size_t)i * m + j] : 0.f;
+            }
+            const int nparts = MODE == 1 ? tg.nparts : 1;
+#pragma unroll 1
+            for (int part = 0; part < nparts; ++part) {
+                const int c0 = part * tg.part_cols;
+                const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
+                __syncthreads();
+                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+                __syncthreads();
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) {
+                    keep_packed(pk[l]);
+#pragma unroll
+                    for (int t = 0; t < K; ++t) {
+                        const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
+                        if (MODE == 0 || c < cols) acc[l][t] = fmaf(gv[l], lds_val(lds, c), acc[l][t]);
+                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        }
+    }
+    uint32_t* tr = reinterpret_cast<uint32_t*>(lds_raw);
+#pragma unroll
+    for (int l = 0; l < LPT; ++l) {
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < K; ++t) tr[threadIdx.x * (K + 1) + t] = __float_as_uint(acc[l][t]);
+        __syncthreads();
+        lds_to_rows<K, NT, ATOMIC>(tr, grad_W, j0 + (int64_t)l * NT, m);
+    }
+}
+
+// any k, any d: one thread per connection
+template <int NT, typename TS, bool ATOMIC>
+__global__ void __launch_bounds__(NT)
+k_backward_weight_generic(const float* __restrict__ g, const TS* __restrict__ x,
+                          const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m,
+                          int d, int k, int b, TileGeom tg) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    TS* lds = reinterpret_cast<TS*>(lds_raw);
+    const int64_t N = m * k;
+    const int64_t e = (int64_t)blockIdx.x * NT + threadIdx.x;
+    const int64_t ee = e < N ? e : N - 1;
+    const int64_t j = ee / k;
+    const uint32_t col = (uint32_t)idx[ee];
+    const int i_begin = blockIdx.y * tg.inst_per_group;
+    const int i_end = min(b, i_begin + tg.inst_per_group);
+    float acc = 0.f;
+    for (int i = i_begin; i < i_end; ++i) {
+        const float gv = g[(size_t)i * m + j];
+        for (int part = 0; part < tg.nparts; ++part) {
+            const int c0 = part * tg.part_cols;
+            const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
+            __syncthreads();
+            stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+            __syncthreads();
+            const uint32_t c = col - (uint32_t)c0;
+            if (c < cols) acc = fmaf(gv, lds_val(lds, c), acc);
+        }
+    }
+    if (e < N) {
+        if (ATOMIC) unsafeAtomicAdd(grad_W + e, acc);
+        else grad_W[e] = acc;
+    }
+}
+
+__global__ void k_fill_zero(float* __restrict__ p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t s = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += s) p[i] = 0.f;
+}
+
+// Picks how rows are tiled / sliced through LDS and how instances are spread over blockIdx.y.
+TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, size_t* lds_bytes,
+              int* groups, bool multi_row = false) {
+    TileGeom tg;
+    const size_t row_bytes = (size_t)c->d * esize;
+    tg.vec_ok = (row_bytes % 16 == 0) && (((uintptr_t)x) % 16 == 0);
+    if (row_bytes <= (size_t)USL_ROW_LDS_BYTES) {
+        tg.nparts = 1;
+        tg.part_cols = c->d;
+        // small rows: several per tile, but keep the tile at 32 KiB so more than one workgroup
+        // fits a compute unit
+        int rpt = multi_row ? (int)((size_t)32768 / row_bytes) : 1;
+        tg.rows_per_tile = rpt < 1 ? 1 : rpt;
+    } else {
+        tg.part_cols = USL_ROW_LDS_BYTES / esize;
+        tg.nparts = (c->d + tg.part_cols - 1) / tg.part_cols;
+        tg.rows_per_tile = 1;
+    }
+    // enough workgroups to fill the chip: split the batch when there are few label blocks
+    const int64_t want = (int64_t)c->num_cu * (row_bytes > 40960 ? 1 : 2);
+    int G = 1;
+    if (nblk * 4 < want * 3) {
+        G = (int)((want + nblk - 1) / nblk);
+        if (G > b) G = b;
+    }
+    tg.inst_per_group = (b + G - 1) / G;
+    if (tg.rows_per_tile > tg.inst_per_group) tg.rows_per_tile = tg.inst_per_group;
+    G = (b + tg.inst_per_group - 1) / tg.inst_per_group;
+    *groups = G;
+    *lds_bytes = tg.nparts == 1 ? (size_t)tg.rows_per_tile * row_bytes
+                                : (size_t)tg.part_cols * esize;
+    return tg;
+}
+
+inline size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+template <typename KERNEL>
+usl_status allow_lds(usl_ctx* c, KERNEL kern, size_t bytes) {
+    if (bytes > 65536)
+        USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    return USL_OK;
+}
+
+template <int K, int LPT, int NT, typename TS>
+usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void* W, float* out,
+                       int b) {
+    const int64_t nblk = (c->m + (int64_t)NT * LPT - 1) / ((int64_t)NT * LPT);
+    size_t lds;
+    int G;
+    TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
+    lds = max_sz(lds, (size_t)NT * (K + 1) * 4);  // row tile, or the idx / W transposition buffer
+    dim3 grid((unsigned)nblk, (unsigned)G);
+#define USL_FW(MODE)                                                                        \
+    do {                                                                                    \
+        USL_TRY(allow_lds(c, k_forward<K, LPT, NT, TS, MODE>, lds));                        \
+        hipLaunchKernelGGL((k_forward<K, LPT, NT, TS, MODE>), grid, dim3(NT), lds, c->stream, \
+                           (const TS*)x, idx, (const TS*)W, out, c->m, c->d, b, tg);        \
+    } while (0)
+    if (tg.nparts > 1) USL_FW(1);
+    else if (LPT == 1 && tg.rows_per_tile > 1) USL_FW(LPT == 1 ? 2 : 0);
+    else USL_FW(0);
+#undef USL_FW
+    return usl_check_launch(c, "forward");
+}
+
+template <typename TS>
+usl_status run_forward_generic(usl_ctx* c, const void* x, const int32_t* idx, const void* W,
+                               float* out, int b) {
+    constexpr int NT = 256;
+    const int64_t nblk = (c->m + NT - 1) / NT;
+    size_t lds;
+    int G;
+    TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G);
+    if (tg.nparts == 1) { lds = (size_t)c->d * sizeof(TS); tg.rows_per_tile = 1; }
+    USL_TRY(allow_lds(c, k_forward_generic<NT, TS>, lds));
+    hipLaunchKernelGGL((k_forward_generic<NT, TS>), dim3((unsigned)nblk, (unsigned)G), dim3(NT), lds,
+                       c->stream, (const TS*)x, idx, (const TS*)W, out, c->m, c->d, c->k, b, tg);
+    return usl_check_launch(c, "forward (generic)");
+}
+
+template <int K, int LPT, int NT, typename TS>
+usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const int32_t* idx,
+                               float* grad_W, int b) {
+    const int64_t nblk = (c->m + (int64_t)NT * LPT - 1) / ((int64_t)NT * LPT);
+    size_t lds;
+    int G;
+    TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
+    lds = max_sz(lds, (size_t)NT * (K + 1) * 4);
+    dim3 grid((unsigned)nblk, (unsigned)G);
+    if (G > 1) {
+        hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W,
+                           (size_t)c->m * c->k);
+    }
+#define USL_BW(MODE, AT)                                                                       \
+    do {                                                                                       \
+        USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT>, lds));               \
+        hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT>), grid, dim3(NT), lds, \
+                           c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg);        \
+    } while (0)
+    const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : 0);
+    if (mode == 1) { if (G > 1) USL_BW(1, true); else USL_BW(1, false); }
+    else if (mode == 2) { if (G > 1) USL_BW(LPT == 1 ? 2 : 0, true); else USL_BW(LPT == 1 ? 2 : 0, false); }
+    else { if (G > 1) USL_BW(0, true); else USL_BW(0, false); }
+#undef USL_BW
+    return usl_check_launch(c, "backward_weight");
+}
+
+template <typename TS>
+usl_status run_backward_weight_generic(usl_ctx* c, const float* g, const void* x,
+                                       const int32_t* idx, float* grad_W, int b) {
+    constexpr int NT = 256;
+    const int64_t N = c->m * (int64_t)c->k;
+    const int64_t nblk = (N + NT - 1) / NT;
+    size_t lds;
+    int G;
+    TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G);
+    if (tg.nparts == 1) { lds = (size_t)c->d * sizeof(TS); tg.rows_per_tile = 1; }
+    dim3 grid((unsigned)nblk, (unsigned)G);
+    if (G > 1) {
+        hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W, (size_t)N);
+        USL_TRY(allow_lds(c, k_backward_weight_generic<NT, TS, true>, lds));
+        hipLaunchKernelGGL((k_backward_weight_generic<NT, TS, true>), grid, dim3(NT), lds, c->stream,
+                           g, (const TS*)x, idx, grad_W, c->m, c->d, c->k, b, tg);
+    } else {
+        USL_TRY(allow_lds(c, k_backward_weight_generic<NT, TS, false>, lds));
+        hipLaunchKernelGGL((k_backward_weight_generic<NT, TS, false>), grid, dim3(NT), lds, c->stream,
+                           g, (const TS*)x, idx, grad_W, c->m, c->d, c->k, b, tg);
+    }
+    return usl_check_launch(c, "backward_weight (generic)");
+}
+
+// The register-resident kernels need k in {8,16,32,64}, indices that fit 16 bits, and 16-byte
+// aligned idx / W rows (guaranteed by k % 8 == 0 for allocations aligned to 16 bytes).
+bool fast_path_ok(const usl_ctx* c, const void* idx, const void* W) {
+    return c->d <= 65536 && (c->k == 8 || c->k == 16 || c->k == 32 || c->k == 64) &&
+           ((uintptr_t)idx % 16 == 0) && (W == nullptr || (uintptr_t)W % 16 == 0);
+}
+
+template <typename TS>
+usl_status forward_t(usl_ctx* c, const void* x, const int32_t* idx, const void* W, float* out, int b) {
+    if (!fast_path_ok(c, idx, W)) return run_forward_generic<TS>(c, x, idx, W, out, b);
+    const bool big = c->m >= (int64_t)c->num_cu * 1024;
+    switch (c->k) {
+        case 8:  return big ? run_forward<8, 16, 512, TS>(c, x, idx, W, out, b) : run_forward<8, 1, 256, TS>(c, x, idx, W, out, b);
+        case 16: return big ? run_forward<16, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<16, 1, 256, TS>(c, x, idx, W, out, b);
+        case 32: return big ? run_forward<32, 4, 512, TS>(c, x, idx, W, out, b) : run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
+        default: return big ? run_forward<64, 2, 512, TS>(c, x, idx, W, out, b) : run_forward<64, 1, 256, TS>(c, x, idx, W, out, b);
+    }
+}
+
+template <typename TS>
+usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const int32_t* idx,
+                             float* grad_W, int b) {
+    if (!fast_path_ok(c, idx, nullptr) || (uintptr_t)grad_W % 16 != 0)
+        return run_backward_weight_generic<TS>(c, g, x, idx, grad_W, b);
+    const bool big = c->m >= (int64_t)c->num_cu * 1024;
+    switch (c->k) {
+        case 8:  return big ? run_backward_weight<8, 16, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        case 32: return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b);
+    }
+}
+
+}  // namespace
+
+usl_status usl_launch_forward(usl_ctx* c, const void* x, const int32_t* idx, const void* W,
+                              float* out, int32_t b) {
+    return c->storage == USL_F32 ? forward_t<float>(c, x, idx, W, out, b)
+                                 : forward_t<uint16_t>(c, x, idx, W, out, b);
+}
+
+usl_status usl_launch_backward_weight(usl_ctx* c, const float* g, const void* x,
+                                      const int32_t* idx, float* grad_W, int32_t b) {
+    return c->storage == USL_F32 ? backward_weight_t<float>(c, g, x, idx, grad_W, b)
+                                 : backward_weight_t<uint16_t>(c, g, x, idx, grad_W, b);
+}

@@ -1,0 +1,201 @@
+// Host layer of libusl: the C ABI, argument checks, context and scratch management.
+#include <math.h>
+#include <stdlib.h>
+
+#include "usl_internal.h"
+
+extern "C" const char* usl_version(void) { return "usl 0.1 (gfx950)"; }
+
+extern "C" usl_status usl_create(usl_ctx** out, int64_t m, int32_t d, int32_t k, int32_t max_b,
+                                 usl_dtype storage, void* hip_stream) {
+    if (!out) return USL_EINVAL;
+    *out = nullptr;
+    if (storage != USL_F32 && storage != USL_BF16) return USL_EINVAL;
+    if (m < 1 || d < 1 || k < 1 || max_b < 1) return USL_EINVAL;
+    if (k > d || d > (1 << 24) || m > 0x7FFFFFFFll) return USL_ESHAPE;
+    if (m * (int64_t)k >= (int64_t)1 << 32) return USL_ESHAPE;
+    usl_ctx* c = (usl_ctx*)calloc(1, sizeof(usl_ctx));
+    if (!c) return USL_ENOMEM;
+    c->m = m; c->d = d; c->k = k; c->max_b = max_b;
+    c->storage = (int)storage;
+    c->stream = (hipStream_t)hip_stream;
+    c->device = -1;
+    c->err[0] = 0;
+    *out = c;
+    return USL_OK;
+}
+
+extern "C" usl_status usl_destroy(usl_ctx* c) {
+    if (!c) return USL_OK;
+    if (c->device >= 0) {
+        void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
+                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->gT, c->gxT};
+        (void)hipStreamSynchronize(c->stream);
+        for (void* p : bufs)
+            if (p) (void)hipFree(p);
+    }
+    free(c);
+    return USL_OK;
+}
+
+extern "C" usl_status usl_set_stream(usl_ctx* c, void* hip_stream) {
+    if (!c) return USL_EINVAL;
+    c->stream = (hipStream_t)hip_stream;
+    return USL_OK;
+}
+
+extern "C" const char* usl_last_error(const usl_ctx* c) { return c ? c->err : "null context"; }
+
+extern "C" usl_status usl_invalidate(usl_ctx* c) {
+    if (!c) return USL_EINVAL;
+    c->csc_built_for = nullptr;
+    return USL_OK;
+}
+
+usl_status usl_prepare_device(usl_ctx* c) {
+    if (c->device >= 0) return USL_OK;
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || n < 1) USL_FAIL(c, USL_EHIP, "no HIP device available");
+    int dev = 0;
+    USL_HIP(c, hipGetDevice(&dev));
+    hipDeviceProp_t p;
+    USL_HIP(c, hipGetDeviceProperties(&p, dev));
+    if ((size_t)p.sharedMemPerBlock < (size_t)USL_ROW_LDS_BYTES + 1024)
+        USL_FAIL(c, USL_EUNSUPPORTED, "device offers %zu bytes of LDS per workgroup, need %d",
+                 (size_t)p.sharedMemPerBlock, USL_ROW_LDS_BYTES + 1024);
+    c->num_cu = p.multiProcessorCount;
+    c->device = dev;
+    return USL_OK;
+}
+
+usl_status usl_reserve(usl_ctx* c, void** buf, size_t* cap, size_t bytes) {
+    if (*buf && *cap >= bytes) return USL_OK;
+    if (*buf) {
+        USL_HIP(c, hipStreamSynchronize(c->stream));
+        USL_HIP(c, hipFree(*buf));
+        *buf = nullptr;
+        *cap = 0;
+    }
+    hipError_t e = hipMalloc(buf, bytes);
+    if (e != hipSuccess) {
+        *buf = nullptr;
+        USL_FAIL(c, USL_ENOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    }
+    *cap = bytes;
+    return USL_OK;
+}
+
+usl_status usl_check_launch(usl_ctx* c, const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) USL_FAIL(c, USL_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return USL_OK;
+}
+
+static usl_status check_batch(usl_ctx* c, int32_t b) {
+    if (b < 1) USL_FAIL(c, USL_EINVAL, "batch size %d < 1", b);
+    if (b > c->max_b) USL_FAIL(c, USL_ESHAPE, "batch size %d exceeds max_b %d", b, c->max_b);
+    return USL_OK;
+}
+
+#define NEED(ptr)                                                          \
+    do {                                                                   \
+        if (!(ptr)) USL_FAIL(c, USL_EINVAL, "argument %s is NULL", #ptr);  \
+    } while (0)
+
+extern "C" usl_status usl_init_indices(usl_ctx* c, int32_t* idx, uint64_t seed) {
+    if (!c) return USL_EINVAL;
+    NEED(idx);
+    USL_TRY(usl_prepare_device(c));
+    c->csc_built_for = nullptr;
+    return usl_launch_init_indices(c, idx, seed);
+}
+
+extern "C" usl_status usl_forward(usl_ctx* c, const void* x, const int32_t* idx, const void* W,
+                                  float* out, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(x); NEED(idx); NEED(W); NEED(out);
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_forward(c, x, idx, W, out, b);
+}
+
+extern "C" usl_status usl_bce_loss_grad(usl_ctx* c, const float* out, const int64_t* tgt_off,
+                                        const int32_t* tgt_lab, float scale, float* g, float* loss,
+                                        int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(out); NEED(tgt_off); NEED(tgt_lab); NEED(g); NEED(loss);
+    if (!(scale == scale) || isinf(scale)) USL_FAIL(c, USL_EINVAL, "scale is not finite");
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_bce(c, out, tgt_off, tgt_lab, scale, g, loss, b);
+}
+
+extern "C" usl_status usl_backward_weight(usl_ctx* c, const float* g, const void* x,
+                                          const int32_t* idx, float* grad_W, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(g); NEED(x); NEED(idx); NEED(grad_W);
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_backward_weight(c, g, x, idx, grad_W, b);
+}
+
+extern "C" usl_status usl_backward_input(usl_ctx* c, const float* g, const int32_t* idx,
+                                         const void* W, float* grad_x, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(g); NEED(idx); NEED(W); NEED(grad_x);
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_backward_input(c, g, idx, W, grad_x, b);
+}
+
+extern "C" usl_status usl_adam_step(usl_ctx* c, void* W, const float* grad_W, float* m1, float* m2,
+                                    int64_t t, float lr, float beta1, float beta2, float eps) {
+    if (!c) return USL_EINVAL;
+    NEED(W); NEED(grad_W); NEED(m1); NEED(m2);
+    if (t < 1) USL_FAIL(c, USL_EINVAL, "step number t=%lld < 1", (long long)t);
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        USL_FAIL(c, USL_EINVAL, "beta1/beta2 must lie in [0,1)");
+    if (!(eps >= 0.f) || !(lr == lr)) USL_FAIL(c, USL_EINVAL, "eps < 0 or lr is NaN");
+    USL_TRY(usl_prepare_device(c));
+    // bias corrections in double on the host; the kernel multiplies by their reciprocals
+    double c1 = 1.0 - pow((double)beta1, (double)t);
+    double c2 = 1.0 - pow((double)beta2, (double)t);
+    return usl_launch_adam(c, W, grad_W, m1, m2, lr, beta1, beta2, eps, (float)(1.0 / c1),
+                           (float)(1.0 / c2));
+}
+
+extern "C" usl_status usl_redistribute(usl_ctx* c, int32_t* idx, void* W, float* m1, float* m2,
+                                       double fraction, uint64_t seed, uint64_t epoch,
+                                       int64_t* n_rewired_host) {
+    if (!c) return USL_EINVAL;
+    NEED(idx); NEED(W); NEED(m1); NEED(m2);
+    if (!(fraction >= 0.0 && fraction <= 1.0))
+        USL_FAIL(c, USL_EINVAL, "fraction %g outside [0,1]", fraction);
+    if (epoch == ~(uint64_t)0) USL_FAIL(c, USL_EINVAL, "epoch 2^64-1 is reserved for usl_init_indices");
+    int64_t N = c->m * (int64_t)c->k;
+    int64_t n = (int64_t)floor(fraction * (double)N);
+    if (n > N) n = N;
+    if (n_rewired_host) *n_rewired_host = n;
+    if (n == 0) return USL_OK;
+    USL_TRY(usl_prepare_device(c));
+    c->csc_built_for = nullptr;
+    return usl_launch_redistribute(c, idx, W, m1, m2, n, seed, epoch);
+}
+
+extern "C" usl_status usl_validate_indices(usl_ctx* c, const int32_t* idx, int64_t* n_bad_host) {
+    if (!c) return USL_EINVAL;
+    NEED(idx); NEED(n_bad_host);
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_validate(c, idx, n_bad_host);
+}
+
+extern "C" usl_status usl_philox_words(usl_ctx* c, const uint32_t* ctr, uint32_t key0,
+                                       uint32_t key1, uint32_t* out, int64_t n) {
+    if (!c) return USL_EINVAL;
+    NEED(ctr); NEED(out);
+    if (n < 0) USL_FAIL(c, USL_EINVAL, "n < 0");
+    if (n == 0) return USL_OK;
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_philox(c, ctr, key0, key1, out, n);
+}

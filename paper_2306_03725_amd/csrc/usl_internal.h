@@ -1,0 +1,99 @@
+// Internal declarations shared by the host layer and the kernel files of libusl.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/usl.h"
+
+// Largest slice of LDS one workgroup uses to hold activation rows.  gfx950 has 160 KiB per
+// compute unit; 128 KiB is one float32 row of 32768 features.
+static constexpr int USL_ROW_LDS_BYTES = 128 * 1024;
+
+struct usl_ctx {
+    int64_t m;
+    int32_t d, k, max_b;
+    int storage;  // usl_dtype
+    hipStream_t stream;
+    int device;        // -1 until the first launch
+    int num_cu;
+    char err[512];
+
+    // --- device scratch, allocated on first use, freed by usl_destroy ---
+    double* bce_partials;     size_t bce_partials_cap;   // per-block loss sums
+    uint32_t* sel_hist;       // radix-select histograms + state
+    uint8_t* prune_flags;     // [m*k] 1 = slot removed by the current redistribution
+    uint32_t* tie_counts;     size_t tie_counts_cap;
+    int64_t* counter64;       // small device counter (validate)
+    // transposed (column-major) connectivity for backward_input
+    uint32_t* csc_ptr;        // [d+1] start of each column's list
+    uint32_t* csc_cursor;     // [d]
+    uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by column
+    int32_t* csc_label;       // [m*k] label j of that slot
+    const int32_t* csc_built_for;  // idx pointer the lists were built from (NULL = stale)
+    float* gT;                size_t gT_cap;   // [m][bp] transposed upstream gradient
+    float* gxT;               size_t gxT_cap;  // [d][bp] transposed input gradient
+};
+
+#define USL_FAIL(ctx, code, ...)                                   \
+    do {                                                           \
+        snprintf((ctx)->err, sizeof((ctx)->err), __VA_ARGS__);     \
+        return (code);                                             \
+    } while (0)
+
+#define USL_HIP(ctx, call)                                                              \
+    do {                                                                                \
+        hipError_t e_ = (call);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            USL_FAIL(ctx, USL_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+
+#define USL_TRY(expr)                     \
+    do {                                  \
+        usl_status s_ = (expr);           \
+        if (s_ != USL_OK) return s_;      \
+    } while (0)
+
+// Makes the device current on first use and reads its compute-unit count.
+usl_status usl_prepare_device(usl_ctx* ctx);
+// Grows *buf to at least `bytes` (old contents are dropped).
+usl_status usl_reserve(usl_ctx* ctx, void** buf, size_t* cap, size_t bytes);
+usl_status usl_check_launch(usl_ctx* ctx, const char* what);
+
+// Kernel launchers (one per file).  All take validated arguments.
+usl_status usl_launch_forward(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W,
+                              float* out, int32_t b);
+usl_status usl_launch_backward_weight(usl_ctx* ctx, const float* g, const void* x,
+                                      const int32_t* idx, float* grad_W, int32_t b);
+usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx,
+                                     const void* W, float* grad_x, int32_t b);
+usl_status usl_launch_bce(usl_ctx* ctx, const float* out, const int64_t* tgt_off,
+                          const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
+usl_status usl_launch_adam(usl_ctx* ctx, void* W, const float* grad_W, float* m1, float* m2,
+                           float lr, float beta1, float beta2, float eps, float inv_c1,
+                           float inv_c2);
+usl_status usl_launch_redistribute(usl_ctx* ctx, int32_t* idx, void* W, float* m1, float* m2,
+                                   int64_t n, uint64_t seed, uint64_t epoch);
+usl_status usl_launch_init_indices(usl_ctx* ctx, int32_t* idx, uint64_t seed);
+usl_status usl_launch_validate(usl_ctx* ctx, const int32_t* idx, int64_t* n_bad_host);
+usl_status usl_launch_philox(usl_ctx* ctx, const uint32_t* ctr, uint32_t key0, uint32_t key1,
+                             uint32_t* out, int64_t n);
+
+// ---- small device helpers -------------------------------------------------------------------
+__device__ __forceinline__ float usl_bf16_to_f32(uint16_t v) {
+    return __uint_as_float((uint32_t)v << 16);
+}
+__device__ __forceinline__ uint16_t usl_f32_to_bf16(float f) {  // nearest, ties to even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <typename TS> __device__ __forceinline__ float usl_load_f32(const TS* p, size_t i);
+template <> __device__ __forceinline__ float usl_load_f32<float>(const float* p, size_t i) {
+    return p[i];
+}
+template <> __device__ __forceinline__ float usl_load_f32<uint16_t>(const uint16_t* p, size_t i) {
+    return usl_bf16_to_f32(p[i]);
+}

@@ -1,0 +1,308 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on the
+same seeded inputs.  Tolerances: 1e-5 for out, g, loss, grad_W; 1e-4 for grad_x and the Adam
+state; connectivity bit-exact.  An element passes if |a-r| <= rtol*|r| + rtol*rms(r)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import assert_close, read_blocks
+
+pytestmark = pytest.mark.gpu
+
+# (m, d, k, b): the code paths they reach are noted; sizes span several tiles and ragged tails
+SHAPES = {
+    "tiny": (1024, 64, 8, 16),                 # config 0
+    "ragged_small": (3001, 1000, 32, 37),      # one label per lane, several rows per stage
+    "odd_d": (777, 333, 16, 5),                # rows not 16-byte aligned: scalar staging
+    "k5": (500, 200, 5, 7),                    # k outside {8,16,32,64}: generic kernels
+    "k33": (300, 100, 33, 4),
+    "k_eq_d": (100, 80, 80, 3),                # k > 64 and k == d
+    "k64": (2500, 4096, 64, 6),
+    "big_blocks": (270001, 2048, 32, 9),       # register-resident blocks, batch split over blocks
+    "big_one_group": (790001, 256, 32, 3),     # enough label blocks: no batch split
+    "sliced_big": (270001, 65536, 32, 2),      # row larger than the LDS budget
+    "sliced_small": (2000, 40000, 16, 3),
+    "wide_d": (1000, 70000, 8, 2),             # d > 65536: indices do not fit 16 bits
+    "one": (1, 1, 1, 1),
+}
+
+
+def make(name, storage="f32"):
+    m, d, k, b = SHAPES[name]
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=min(3, m), index=10 + list(SHAPES).index(name))
+    return cfg
+
+
+@pytest.fixture(scope="module")
+def usl():
+    from paper_2306_03725_amd import usl as u
+    assert torch.cuda.is_available()
+    return u
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+CASES = [(n, "f32") for n in SHAPES] + [(n, "bf16") for n in ("tiny", "ragged_small", "k5", "k64", "big_blocks", "sliced_small")]
+
+
+@pytest.mark.parametrize("name,storage", CASES)
+def test_forward_backward_products(usl, gu, orc, name, storage):
+    cfg = make(name, storage)
+    print("case", name, storage, cfg.m, cfg.d, cfg.k, cfg.b, flush=True)
+    idx, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
+    L = usl.Layer(cfg.m, cfg.d, cfg.k, cfg.b, storage)
+    d_idx, d_W, d_x, d_g = gu.dev(idx), gu.dev(W), gu.dev(x), gu.dev(g)
+    out = gu.empty((cfg.b, cfg.m)).fill_(float("nan"))
+    gW = gu.empty((cfg.m, cfg.k)).fill_(float("nan"))
+    gx = gu.empty((cfg.b, cfg.d)).fill_(float("nan"))
+    L.forward(d_x, d_idx, d_W, out, cfg.b)
+    L.backward_weight(d_g, d_x, d_idx, gW, cfg.b)
+    L.backward_input(d_g, d_idx, d_W, gx, cfg.b)
+    torch.cuda.synchronize()
+    assert_close(gu.host(out), orc.forward(x, idx, W), 1e-5, "out")
+    assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W")
+    assert_close(gu.host(gx), orc.backward_input(g, idx, W, cfg.d), 1e-4, "grad_x")
+    # inputs untouched
+    np.testing.assert_array_equal(gu.host(d_idx), idx)
+    np.testing.assert_array_equal(gu.host(d_W), W)
+    L.close()
+
+
+def test_fig1c_through_the_library(usl, gu):
+    blk = read_blocks("fig1c_uniform_format.txt")
+    idx = np.ascontiguousarray(blk["indices s x m"].T.astype(np.int32))
+    W = np.ascontiguousarray(blk["weights s x m"].T.astype(np.float32))
+    L = usl.Layer(5, 4, 2, 4)
+    out = gu.empty((4, 5))
+    L.forward(gu.dev(np.eye(4, dtype=np.float32)), gu.dev(idx), gu.dev(W), out, 4)
+    np.testing.assert_array_equal(gu.host(out), blk["dense feature x label"].astype(np.float32))
+
+
+def test_smaller_batch_than_max_and_reuse(usl, gu, orc):
+    """One context, several batch sizes and index arrays: scratch and the column lists follow."""
+    cfg = make("ragged_small")
+    L = usl.Layer(cfg.m, cfg.d, cfg.k, cfg.b)
+    for sub, index in ((cfg.b, 31), (5, 32), (1, 33)):
+        c2 = wl.custom(cfg.m, cfg.d, cfg.k, sub, index=index)
+        idx, W, x, g = wl.gen_idx(c2), wl.gen_W(c2), wl.gen_x(c2), wl.gen_g(c2)
+        d_idx = gu.dev(idx)
+        out, gx = gu.empty((sub, cfg.m)), gu.empty((sub, cfg.d))
+        L.forward(gu.dev(x), d_idx, gu.dev(W), out, sub)
+        L.backward_input(gu.dev(g), d_idx, gu.dev(W), gx, sub)
+        assert_close(gu.host(out), orc.forward(x, idx, W), 1e-5, "out")
+        assert_close(gu.host(gx), orc.backward_input(g, idx, W, cfg.d), 1e-4, "grad_x")
+    # same buffer, new contents: the caller must say so
+    idx2 = wl.gen_idx(wl.custom(cfg.m, cfg.d, cfg.k, 1, index=34))
+    d_idx.copy_(torch.from_numpy(idx2))
+    L.invalidate()
+    L.backward_input(gu.dev(g), d_idx, gu.dev(W), gx, 1)
+    assert_close(gu.host(gx), orc.backward_input(g, idx2, W, cfg.d), 1e-4, "grad_x after invalidate")
+
+
+@pytest.mark.parametrize("name", ["tiny", "ragged_small", "odd_d", "big_blocks", "one"])
+def test_bce(usl, gu, orc, name):
+    cfg = make(name)
+    m, b = cfg.m, cfg.b
+    r = wl.rng(cfg, 7)
+    out = (r.standard_normal((b, m)) * 3).astype(np.float32)
+    out.reshape(-1)[:: max(1, out.size // 50)] = r.choice([0.0, 40.0, -40.0, 90.0, -90.0], size=len(out.reshape(-1)[:: max(1, out.size // 50)]))
+    off, lab = wl.gen_targets(cfg)
+    if name == "ragged_small":   # an instance without positives, repeated ids, a dense instance
+        lists = [list(lab[off[i]:off[i + 1]]) for i in range(b)]
+        lists[0] = []
+        lists[1] = lists[1] + lists[1][:2]
+        lists[2] = list(range(0, m, 3))            # more positives in one chunk than the LDS list holds
+        off = np.cumsum([0] + [len(l) for l in lists]).astype(np.int64)
+        lab = np.array([v for l in lists for v in l], np.int32)
+    scale = float(np.float32(1.0 / b))
+    L = usl.Layer(m, cfg.d, cfg.k, b)
+    d_out, d_off, d_lab = gu.dev(out), gu.dev(off), gu.dev(lab if lab.size else np.zeros(1, np.int32))
+    g = gu.empty((b, m))
+    loss = gu.empty((1,))
+    L.bce_loss_grad(d_out, d_off, d_lab, scale, g, loss, b)
+    ref_loss, ref_g = orc.bce_loss_grad(out, off, lab, scale)
+    assert_close(gu.host(g), ref_g, 1e-5, "g")
+    assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
+    # in place
+    L.bce_loss_grad(d_out, d_off, d_lab, scale, d_out, loss, b)
+    np.testing.assert_array_equal(gu.host(d_out), gu.host(g))
+    assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("n_shape", [(1024, 8), (777, 5), (3, 1), (30938, 32)])
+def test_adam(usl, gu, orc, n_shape, storage):
+    m, k = n_shape
+    cfg = wl.custom(m, max(k, 64), k, 1, storage=storage, index=40)
+    r = wl.rng(cfg, 8)
+    W = wl.gen_W(cfg)
+    m1 = np.zeros((m, k), np.float32)
+    m2 = np.zeros((m, k), np.float32)
+    L = usl.Layer(m, cfg.d, k, 1, storage)
+    d_W, d_m1, d_m2 = gu.dev(W), gu.dev(m1), gu.dev(m2)
+    hp = wl.ADAM
+    for t in range(1, 6):
+        gw = (r.standard_normal((m, k)) * 10.0 ** r.integers(-5, 1, (m, k))).astype(np.float32)
+        gw[r.random((m, k)) < 0.1] = 0.0
+        # teacher forcing: the oracle starts every step from the state the GPU holds
+        W, m1, m2 = gu.host(d_W).copy(), gu.host(d_m1).copy(), gu.host(d_m2).copy()
+        pre = orc.adam_step(W, gw, m1, m2, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        L.adam_step(d_W, gu.dev(gw), d_m1, d_m2, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        assert_close(gu.host(d_m1), m1, 1e-4, "m1 step %d" % t)
+        assert_close(gu.host(d_m2), m2, 1e-4, "m2 step %d" % t)
+        if storage == "f32":
+            assert_close(gu.host(d_W), W, 1e-4, "W step %d" % t)
+        else:   # the stored bfloat16 may differ by one unit in the last place where the float sits on a tie
+            got = wl.bf16_bits_to_f32(gu.host(d_W)).astype(np.float64)
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(pre), 1e-30))) - 7)
+            assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre)).all()
+
+
+def test_philox_words(usl, gu):
+    from helpers import py_philox
+    r = np.random.default_rng(3)
+    ctr = r.integers(0, 2 ** 32, size=(500, 4), dtype=np.uint64).astype(np.uint32)
+    ctr[0] = 0
+    ctr[1] = 0xFFFFFFFF
+    key = (int(r.integers(0, 2 ** 32)), int(r.integers(0, 2 ** 32)))
+    L = usl.Layer(8, 8, 1, 1)
+    out = gu.empty((500, 4), torch.int32)
+    L.philox_words(gu.dev(ctr.view(np.int32)), key[0], key[1], out, 500)
+    got = gu.host(out).view(np.uint32)
+    for i in range(500):
+        assert tuple(int(v) for v in got[i]) == py_philox([int(v) for v in ctr[i]], key)
+    out0 = gu.empty((1, 4), torch.int32)
+    L.philox_words(gu.dev(np.zeros((1, 4), np.int32)), 0, 0, out0, 1)
+    assert [hex(v) for v in gu.host(out0).view(np.uint32)[0]] == ["0x6627e8d5", "0xe169c58d", "0xbc57ac4c", "0x9b00dbd8"]
+
+
+@pytest.mark.parametrize("m,d,k", [(1024, 64, 8), (3001, 1000, 32), (500, 200, 5), (300, 100, 33), (100, 80, 80),
+                                   (50, 9, 9), (2500, 4096, 64), (7, 3, 1), (30938, 1024, 32)])
+def test_init_indices_bit_exact(usl, gu, orc, m, d, k):
+    seed = 0xC0FFEE1234567
+    L = usl.Layer(m, d, k, 1)
+    idx = gu.empty((m, k), torch.int32).fill_(-7)
+    L.init_indices(idx, seed)
+    got = gu.host(idx)
+    np.testing.assert_array_equal(got, orc.init_indices(m, d, k, seed))
+    assert L.validate_indices(idx) == 0 and orc.count_bad_rows(got, d) == 0
+    bad = got.copy()
+    bad[0, 0] = d
+    if k > 1:
+        bad[m - 1, k - 1] = bad[m - 1, 0]
+    assert L.validate_indices(gu.dev(bad)) == orc.count_bad_rows(bad, d) > 0
+
+
+REDIST = [("tiny", "f32", 0.10), ("tiny", "bf16", 0.10), ("ragged_small", "f32", 0.05), ("ragged_small", "bf16", 0.2),
+          ("k5", "f32", 0.33), ("k33", "f32", 0.5), ("k_eq_d", "f32", 0.9), ("k64", "bf16", 0.05),
+          ("big_blocks", "f32", 0.05), ("one", "f32", 1.0), ("tiny", "f32", 1.0), ("tiny", "f32", 0.0)]
+
+
+@pytest.mark.parametrize("name,storage,frac", REDIST)
+def test_redistribute_bit_exact(usl, gu, orc, name, storage, frac):
+    cfg = make(name, storage)
+    m, d, k = cfg.m, cfg.d, cfg.k
+    idx, W = wl.gen_idx(cfg), wl.gen_W(cfg)
+    Wf = wl.as_f32(W).copy().reshape(-1)
+    if Wf.size > 200:   # ties at the threshold, signed zeros, a NaN
+        Wf[5], Wf[11], Wf[17] = 0.0, -0.0, np.float32("nan")
+        fin = np.sort(np.abs(Wf[np.isfinite(Wf)]))
+        q = fin[min(fin.size - 1, max(0, int(frac * Wf.size) - 1))]
+        Wf[100:160] = q * np.where(np.arange(60) % 2, 1, -1)
+    W = wl.store(Wf.reshape(m, k), storage)
+    r = wl.rng(cfg, 9)
+    m1 = r.standard_normal((m, k)).astype(np.float32)
+    m2 = r.random((m, k)).astype(np.float32)
+    seed, epoch = wl.redistribution_seed(cfg), 3
+    L = usl.Layer(m, d, k, cfg.b, storage)
+    d_idx, d_W, d_m1, d_m2 = gu.dev(idx), gu.dev(W), gu.dev(m1), gu.dev(m2)
+    n = L.redistribute(d_idx, d_W, d_m1, d_m2, frac, seed, epoch)
+    n_ref, flags = orc.redistribute(idx, W, m1, m2, d, frac, seed, epoch)     # in place on the host copies
+    assert n == n_ref == int(np.floor(frac * m * k))
+    np.testing.assert_array_equal(gu.host(d_idx), idx)
+    np.testing.assert_array_equal(gu.host(d_W).view(np.uint8), W.view(np.uint8))
+    np.testing.assert_array_equal(gu.host(d_m1).view(np.uint8), m1.view(np.uint8))
+    np.testing.assert_array_equal(gu.host(d_m2).view(np.uint8), m2.view(np.uint8))
+    assert L.validate_indices(d_idx) == 0
+    # the column lists follow the new connectivity
+    g = wl.gen_g(cfg)
+    gx = gu.empty((cfg.b, d))
+    L.backward_input(gu.dev(g), d_idx, d_W, gx, cfg.b)
+    ref, got = orc.backward_input(g, idx, W, d), gu.host(gx)
+    fin = np.isfinite(ref)          # the planted NaN weight poisons one feature on both sides
+    assert np.isnan(got[~fin]).all()
+    assert_close(got[fin], ref[fin], 1e-4, "grad_x after redistribution")
+
+
+def run_schedule(usl, gu, orc, cfg, steps):
+    """Whole train loop on the GPU; before every call the oracle is handed the GPU's current state
+    (teacher forcing), so each call is checked on identical inputs."""
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    hp = wl.ADAM
+    L = usl.Layer(m, d, k, b, cfg.storage)
+    idx0 = orc.init_indices(m, d, k, 11)
+    d_idx = gu.empty((m, k), torch.int32)
+    L.init_indices(d_idx, 11)
+    np.testing.assert_array_equal(gu.host(d_idx), idx0)
+    d_W = gu.dev(wl.gen_W(cfg))
+    d_m1, d_m2 = gu.dev(np.zeros((m, k), np.float32)), gu.dev(np.zeros((m, k), np.float32))
+    out, gW, gx, loss = gu.empty((b, m)), gu.empty((m, k)), gu.empty((b, d)), gu.empty((1,))
+    seed = wl.redistribution_seed(cfg)
+    epoch = 0
+    scale = float(np.float32(1.0 / b))
+    for step in range(1, steps + 1):
+        x = wl.gen_x(cfg, step % cfg.n_x_batches)
+        off, lab = wl.gen_targets(cfg, step % cfg.n_x_batches)
+        d_x = gu.dev(x)
+        idx, W = gu.host(d_idx).copy(), gu.host(d_W).copy()
+        L.forward(d_x, d_idx, d_W, out, b)
+        h_out = gu.host(out).copy()
+        assert_close(h_out, orc.forward(x, idx, W), 1e-5, "out @%d" % step)
+        L.bce_loss_grad(out, gu.dev(off), gu.dev(lab), scale, out, loss, b)      # in place
+        ref_loss, ref_g = orc.bce_loss_grad(h_out, off, lab, scale)
+        h_g = gu.host(out).copy()
+        assert_close(h_g, ref_g, 1e-5, "g @%d" % step)
+        assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+        L.backward_weight(out, d_x, d_idx, gW, b)
+        L.backward_input(out, d_idx, d_W, gx, b)
+        h_gW = gu.host(gW).copy()
+        assert_close(h_gW, orc.backward_weight(h_g, x, idx), 1e-5, "grad_W @%d" % step)
+        assert_close(gu.host(gx), orc.backward_input(h_g, idx, W, d), 1e-4, "grad_x @%d" % step)
+        m1, m2 = gu.host(d_m1).copy(), gu.host(d_m2).copy()
+        L.adam_step(d_W, gW, d_m1, d_m2, step, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        orc.adam_step(W, h_gW, m1, m2, step, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        if cfg.storage == "f32":
+            assert_close(gu.host(d_W), W, 1e-4, "W @%d" % step)
+        assert_close(gu.host(d_m1), m1, 1e-4, "m1 @%d" % step)
+        assert_close(gu.host(d_m2), m2, 1e-4, "m2 @%d" % step)
+        if wl.is_redistribution_step(cfg, step):
+            idx, W, m1, m2 = (gu.host(t).copy() for t in (d_idx, d_W, d_m1, d_m2))
+            n = L.redistribute(d_idx, d_W, d_m1, d_m2, cfg.fraction, seed, epoch)
+            n_ref, _ = orc.redistribute(idx, W, m1, m2, d, cfg.fraction, seed, epoch)
+            assert n == n_ref
+            np.testing.assert_array_equal(gu.host(d_idx), idx)
+            np.testing.assert_array_equal(gu.host(d_W).view(np.uint8), W.view(np.uint8))
+            np.testing.assert_array_equal(gu.host(d_m1), m1)
+            np.testing.assert_array_equal(gu.host(d_m2), m2)
+            assert L.validate_indices(d_idx) == 0
+            epoch += 1
+    return epoch
+
+
+def test_tiny_schedule(usl, gu, orc):
+    assert run_schedule(usl, gu, orc, wl.CONFIGS["tiny"], 1) == 1
+
+
+def test_medium_schedule_prefix(usl, gu, orc):
+    """Config 1 (m=30938, d=1024, k=32, b=128): 20 of its 100 steps, two redistributions."""
+    assert run_schedule(usl, gu, orc, wl.CONFIGS["medium"], 20) == 2
+
+
+def test_tiny_schedule_bf16(usl, gu, orc):
+    cfg = wl.CONFIGS["tiny"]._replace(storage="bf16", index=7)
+    assert run_schedule(usl, gu, orc, cfg, 3) == 3
