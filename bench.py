@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the uniformly-sparse output layer's train step on one MI355X.
+
+One step = forward + sparse-target BCE (loss and gradient) + backward-weight + backward-input +
+Adam, plus a connection redistribution after every `period`-th step, on seeded synthetic data
+of the headline workload (m=500,000 labels, d=32,768, fan-in k=32, batch 256, float32).
+All inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published peak
+
+
+def algorithmic_bytes(cfg):
+    """Bytes each call has to move at the C-ABI level (x counted once per pass)."""
+    es = 2 if cfg.storage == "bf16" else 4
+    E, N, X = cfg.b * cfg.m, cfg.m * cfg.k, cfg.b * cfg.d
+    per = {
+        "forward": (4 + es) * N + es * X + 4 * E,
+        "bce": 8 * E,
+        "backward_weight": 4 * E + 4 * N + es * X + 4 * N,
+        "backward_input": 4 * E + (4 + es) * N + 4 * X,
+        "adam": (es + 12) * N + (es + 8) * N,
+    }
+    per["step"] = sum(per.values())
+    return per
+
+
+def cpu_baseline(cfg, budget_s=12.0, max_reps=5):
+    """The oracle, as it stands, timed on the host cores on the same workload: whole train steps
+    (forward, BCE, backward-weight, backward-input, Adam) of one full batch, repeated until about
+    `budget_s` seconds of CPU work have been spent."""
+    import oracle
+    import workloads as wl
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    off, lab = wl.gen_targets(cfg)
+    m1 = np.zeros((cfg.m, cfg.k), np.float32)
+    m2 = np.zeros((cfg.m, cfg.k), np.float32)
+    hp = wl.ADAM
+    times = []
+    while len(times) < max_reps and (not times or sum(times) < budget_s):
+        t0 = time.perf_counter()
+        out = oracle.forward(x, idx, W)
+        _, g = oracle.bce_loss_grad(out, off, lab, 1.0 / cfg.b)
+        gW = oracle.backward_weight(g, x, idx)
+        oracle.backward_input(g, idx, W, cfg.d)
+        oracle.adam_step(W, gW, m1, m2, len(times) + 1, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        times.append(time.perf_counter() - t0)
+    per_step = float(np.mean(times))
+    return {"value": 1.0 / per_step, "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d whole train steps (no redistribution) of the same workload, full batch of %d; "
+                      "%.2f s per step" % (len(times), cfg.b, per_step)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large", help="tiny | medium | large | large_wide | stress")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-kib", type=float, default=None,
+                    help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (FETCH+WRITE, scaled)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2306_03725_amd import usl   # raises if libusl.so is not built: no fallback
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    cfg = wl.CONFIGS[args.workload]
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    L = usl.Layer(m, d, k, b, cfg.storage, stream.cuda_stream)
+
+    def up(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---- resident state and inputs
+    idx = torch.empty((m, k), dtype=torch.int32, device=dev)
+    L.init_indices(idx, 1000 * cfg.index + wl.STREAM_IDX)
+    W = up(wl.gen_W(cfg))
+    m1 = torch.zeros((m, k), dtype=torch.float32, device=dev)
+    m2 = torch.zeros((m, k), dtype=torch.float32, device=dev)
+    gW = torch.empty((m, k), dtype=torch.float32, device=dev)
+    xs = [up(wl.gen_x(cfg, i)) for i in range(cfg.n_x_batches)]
+    tg = [tuple(up(a) for a in wl.gen_targets(cfg, i)) for i in range(cfg.n_x_batches)]
+    out = torch.empty((b, m), dtype=torch.float32, device=dev)     # g is written in place
+    gx = torch.empty((b, d), dtype=torch.float32, device=dev)
+    loss = torch.empty((1,), dtype=torch.float32, device=dev)
+    seed = wl.redistribution_seed(cfg)
+    scale = float(np.float32(1.0 / b))
+    hp = wl.ADAM
+    state = {"t": 0, "epoch": 0}
+    calls = ["forward", "bce", "backward_weight", "backward_input", "adam", "redistribute"]
+
+    def step(ev=None):
+        state["t"] += 1
+        t = state["t"]
+        x = xs[t % len(xs)]
+        off, lab = tg[t % len(tg)]
+        marks = []
+
+        def mark():
+            if ev is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                marks.append(e)
+        mark()
+        L.forward(x, idx, W, out, b); mark()
+        L.bce_loss_grad(out, off, lab, scale, out, loss, b); mark()
+        L.backward_weight(out, x, idx, gW, b); mark()
+        L.backward_input(out, idx, W, gx, b); mark()
+        L.adam_step(W, gW, m1, m2, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"]); mark()
+        if wl.is_redistribution_step(cfg, t):
+            L.redistribute(idx, W, m1, m2, cfg.fraction, seed, state["epoch"])
+            state["epoch"] += 1
+            mark()
+        if ev is not None:
+            ev.append(marks)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step(events)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall0) * 1e3
+    total_ms = e0.elapsed_time(e1)
+    loss_value = float(loss.item())
+    n_bad = L.validate_indices(idx)
+
+    per_call = {c: [] for c in calls}
+    for marks in events:
+        for i in range(len(marks) - 1):
+            per_call[calls[i]].append(marks[i].elapsed_time(marks[i + 1]))
+    call_ms = {c: (float(np.mean(v)) if v else None) for c, v in per_call.items()}
+    ab = algorithmic_bytes(cfg)
+    ms_per_step = total_ms / args.steps
+    steps_per_s = 1e3 / ms_per_step
+    # the dominant call and its roofline position (algorithmic bytes / measured time)
+    dom = max((c for c in calls[:5]), key=lambda c: call_ms[c] or 0.0)
+    dom_gbps = ab[dom] / (call_ms[dom] * 1e-3) / 1e9
+    roof = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
+            "ms_per_launch": round(call_ms[dom], 4), "algorithmic_bytes": ab[dom],
+            "traffic": (args.traffic_kib * 1024 if args.traffic_kib is not None else None)}
+    step_gbps = ab["step"] / (ms_per_step * 1e-3) / 1e9
+    res = {
+        "metric": "sparse_layer_train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.storage == "f32" else "bf16 storage, f32 arithmetic", "data": "synthetic",
+        "config": {"workload": "%s: m=%d d=%d k=%d b=%d %s, redistribution of %.0f%% every %d steps"
+                               % (cfg.name, m, d, k, b, cfg.storage, 100 * cfg.fraction, cfg.period),
+                   "parallelism": "single GPU"},
+        "achieved_hbm_GBps": round(step_gbps, 1), "hbm_frac_of_peak": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "algorithmic_GB_per_step": round(ab["step"] / 1e9, 4),
+        "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
+        "call_GBps": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9, 1) for c in calls[:5]},
+        "wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "loss": loss_value, "bad_rows": n_bad, "redistributions": state["epoch"],
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
