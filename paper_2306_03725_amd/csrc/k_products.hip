@@ -12,6 +12,10 @@
 
 namespace {
 
+// Copies n elements from global memory into LDS.  With 16-byte alignment the bulk goes through
+// global_load_lds_dwordx4: each wavefront moves 1 KiB per instruction straight into LDS (the LDS
+// address is wave-uniform, the hardware adds lane*16), no VGPRs are used and all of a lane's loads
+// are in flight together.  The caller's barrier follows the vmcnt wait.
 template <typename TS, int NT>
 __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict__ lds, int n,
                                       bool vec_ok) {
@@ -19,7 +23,14 @@ __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict
         const uint4* s = reinterpret_cast<const uint4*>(src);
         uint4* dd = reinterpret_cast<uint4*>(lds);
         const int nv = (int)((size_t)n * sizeof(TS) / 16);
-        for (int v = threadIdx.x; v < nv; v += NT) dd[v] = s[v];
+        const int full = nv & ~63;
+        const int lane = threadIdx.x & 63;
+        for (int v = (threadIdx.x >> 6) * 64; v < full; v += NT)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(s + v + lane),
+                (__attribute__((address_space(3))) void*)(dd + v), 16, 0, 0);
+        for (int v = full + threadIdx.x; v < nv; v += NT) dd[v] = s[v];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else {
         for (int c = threadIdx.x; c < n; c += NT) lds[c] = src[c];
     }
@@ -70,17 +81,39 @@ __device__ __forceinline__ void lds_to_rows(const uint32_t* __restrict__ lds, fl
     }
 }
 
-// Brings the k indices of NT consecutive labels into registers, two 16-bit indices per register.
+// Private slot order of one label: K bytes (slot visited at step s), held as K/4 words while the
+// registers are being filled.  A null table means natural order.
+template <int K>
+struct SlotOrder {
+    uint32_t w[K / 4];
+    bool on;
+    __device__ __forceinline__ void load(const uint8_t* __restrict__ perm, int64_t j, bool valid) {
+        on = perm != nullptr;
+        if (on) {
+            const uint32_t* p = reinterpret_cast<const uint32_t*>(perm + j * K);
+#pragma unroll
+            for (int q = 0; q < K / 4; ++q) w[q] = valid ? p[q] : (0x03020100u + 0x04040404u * q);
+        }
+    }
+    __device__ __forceinline__ int at(int s) const {
+        return on ? (int)((w[s >> 2] >> (8 * (s & 3))) & 0xFFu) : s;
+    }
+};
+
+// Brings the k indices of NT consecutive labels into registers, two 16-bit indices per register,
+// in the label's private slot order.
 template <int K, int NT>
 __device__ __forceinline__ void fetch_idx_packed(const int32_t* __restrict__ idx, int64_t row0,
-                                                 int64_t m, uint32_t* lds, uint32_t (&pk)[K / 2]) {
+                                                 int64_t m, uint32_t* lds, const SlotOrder<K>& so,
+                                                 uint32_t (&pk)[K / 2]) {
     __syncthreads();
     rows_to_lds<K, NT>(reinterpret_cast<const uint32_t*>(idx), row0, m, lds);
     __syncthreads();
     const bool valid = row0 + threadIdx.x < m;
     const uint32_t* p = lds + threadIdx.x * (K + 1);
 #pragma unroll
-    for (int q = 0; q < K / 2; ++q) pk[q] = valid ? (p[2 * q] | (p[2 * q + 1] << 16)) : 0u;
+    for (int q = 0; q < K / 2; ++q)
+        pk[q] = valid ? (p[so.at(2 * q)] | (p[so.at(2 * q + 1)] << 16)) : 0u;
 }
 template <int K>
 __device__ __forceinline__ uint32_t col_of(const uint32_t (&pk)[K / 2], int t) {
@@ -89,28 +122,28 @@ __device__ __forceinline__ uint32_t col_of(const uint32_t (&pk)[K / 2], int t) {
 
 template <int K, int NT>
 __device__ __forceinline__ void fetch_w(const float* __restrict__ W, int64_t row0, int64_t m,
-                                        uint32_t* lds, float (&w)[K]) {
+                                        uint32_t* lds, const SlotOrder<K>& so, float (&w)[K]) {
     __syncthreads();
     rows_to_lds<K, NT>(reinterpret_cast<const uint32_t*>(W), row0, m, lds);
     __syncthreads();
     const bool valid = row0 + threadIdx.x < m;
     const uint32_t* p = lds + threadIdx.x * (K + 1);
 #pragma unroll
-    for (int t = 0; t < K; ++t) w[t] = valid ? __uint_as_float(p[t]) : 0.f;
+    for (int t = 0; t < K; ++t) w[t] = valid ? __uint_as_float(p[so.at(t)]) : 0.f;
 }
 template <int K, int NT>
 __device__ __forceinline__ void fetch_w(const uint16_t* __restrict__ W, int64_t row0, int64_t m,
-                                        uint32_t* lds, float (&w)[K]) {
+                                        uint32_t* lds, const SlotOrder<K>& so, float (&w)[K]) {
     __syncthreads();
     rows_to_lds<K / 2, NT>(reinterpret_cast<const uint32_t*>(W), row0, m, lds);
     __syncthreads();
     const bool valid = row0 + threadIdx.x < m;
     const uint32_t* p = lds + threadIdx.x * (K / 2 + 1);
 #pragma unroll
-    for (int q = 0; q < K / 2; ++q) {
-        const uint32_t u = valid ? p[q] : 0u;
-        w[2 * q] = __uint_as_float(u << 16);
-        w[2 * q + 1] = __uint_as_float(u & 0xFFFF0000u);
+    for (int t = 0; t < K; ++t) {
+        const int slot = so.at(t);
+        const uint32_t u = valid ? p[slot >> 1] : 0u;
+        w[t] = __uint_as_float((slot & 1) ? (u & 0xFFFF0000u) : (u << 16));
     }
 }
 
@@ -137,7 +170,8 @@ struct TileGeom {
 template <int K, int LPT, int NT, typename TS, int MODE>
 __global__ void __launch_bounds__(NT)
 k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* __restrict__ W,
-          float* __restrict__ out, int64_t m, int d, int b, TileGeom tg) {
+          float* __restrict__ out, int64_t m, int d, int b, TileGeom tg,
+          const uint8_t* __restrict__ perm) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
@@ -146,8 +180,10 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
 #pragma unroll
     for (int l = 0; l < LPT; ++l) {
         const int64_t row0 = j0 + (int64_t)l * NT;
-        fetch_idx_packed<K, NT>(idx, row0, m, reinterpret_cast<uint32_t*>(lds_raw), pk[l]);
-        fetch_w<K, NT>(W, row0, m, reinterpret_cast<uint32_t*>(lds_raw), w[l]);
+        SlotOrder<K> so;
+        so.load(perm, row0 + threadIdx.x, row0 + threadIdx.x < m);
+        fetch_idx_packed<K, NT>(idx, row0, m, reinterpret_cast<uint32_t*>(lds_raw), so, pk[l]);
+        fetch_w<K, NT>(W, row0, m, reinterpret_cast<uint32_t*>(lds_raw), so, w[l]);
     }
     const int64_t jme = j0 + threadIdx.x;  // label of slot l is jme + l*NT
     const int i_begin = blockIdx.y * tg.inst_per_group;
@@ -243,7 +279,7 @@ template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC>
 __global__ void __launch_bounds__(NT)
 k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m, int d,
-                  int b, TileGeom tg) {
+                  int b, TileGeom tg, const uint8_t* __restrict__ perm) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
@@ -251,7 +287,10 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
     float acc[LPT][K];
 #pragma unroll
     for (int l = 0; l < LPT; ++l) {
-        fetch_idx_packed<K, NT>(idx, j0 + (int64_t)l * NT, m, reinterpret_cast<uint32_t*>(lds_raw), pk[l]);
+        const int64_t row0 = j0 + (int64_t)l * NT;
+        SlotOrder<K> so;
+        so.load(perm, row0 + threadIdx.x, row0 + threadIdx.x < m);
+        fetch_idx_packed<K, NT>(idx, row0, m, reinterpret_cast<uint32_t*>(lds_raw), so, pk[l]);
 #pragma unroll
         for (int t = 0; t < K; ++t) acc[l][t] = 0.f;
     }
@@ -311,9 +350,12 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
     uint32_t* tr = reinterpret_cast<uint32_t*>(lds_raw);
 #pragma unroll
     for (int l = 0; l < LPT; ++l) {
+        const int64_t row0 = j0 + (int64_t)l * NT;
+        SlotOrder<K> so;
+        so.load(perm, row0 + threadIdx.x, row0 + threadIdx.x < m);
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < K; ++t) tr[threadIdx.x * (K + 1) + t] = __float_as_uint(acc[l][t]);
+        for (int t = 0; t < K; ++t) tr[threadIdx.x * (K + 1) + so.at(t)] = __float_as_uint(acc[l][t]);
         __syncthreads();
         lds_to_rows<K, NT, ATOMIC>(tr, grad_W, j0 + (int64_t)l * NT, m);
     }
@@ -411,12 +453,14 @@ usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void
     int G;
     TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
     lds = max_sz(lds, (size_t)NT * (K + 1) * 4);  // row tile, or the idx / W transposition buffer
+    if (c->slot_order_for != idx) USL_TRY(usl_build_slot_order(c, idx));
+    const uint8_t* perm = c->slot_order;
     dim3 grid((unsigned)nblk, (unsigned)G);
 #define USL_FW(MODE)                                                                        \
     do {                                                                                    \
         USL_TRY(allow_lds(c, k_forward<K, LPT, NT, TS, MODE>, lds));                        \
         hipLaunchKernelGGL((k_forward<K, LPT, NT, TS, MODE>), grid, dim3(NT), lds, c->stream, \
-                           (const TS*)x, idx, (const TS*)W, out, c->m, c->d, b, tg);        \
+                           (const TS*)x, idx, (const TS*)W, out, c->m, c->d, b, tg, perm);  \
     } while (0)
     if (tg.nparts > 1) USL_FW(1);
     else if (LPT == 1 && tg.rows_per_tile > 1) USL_FW(LPT == 1 ? 2 : 0);
@@ -448,6 +492,8 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     int G;
     TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
     lds = max_sz(lds, (size_t)NT * (K + 1) * 4);
+    if (c->slot_order_for != idx) USL_TRY(usl_build_slot_order(c, idx));
+    const uint8_t* perm = c->slot_order;
     dim3 grid((unsigned)nblk, (unsigned)G);
     if (G > 1) {
         hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W,
@@ -457,7 +503,7 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     do {                                                                                       \
         USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT>, lds));               \
         hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT>), grid, dim3(NT), lds, \
-                           c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg);        \
+                           c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);  \
     } while (0)
     const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : 0);
     if (mode == 1) { if (G > 1) USL_BW(1, true); else USL_BW(1, false); }

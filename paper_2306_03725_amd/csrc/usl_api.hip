@@ -29,7 +29,8 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (!c) return USL_OK;
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
-                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->gT, c->gxT};
+                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->gT, c->gxT,
+                        c->slot_order};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
@@ -49,6 +50,7 @@ extern "C" const char* usl_last_error(const usl_ctx* c) { return c ? c->err : "n
 extern "C" usl_status usl_invalidate(usl_ctx* c) {
     if (!c) return USL_EINVAL;
     c->csc_built_for = nullptr;
+    c->slot_order_for = nullptr;
     return USL_OK;
 }
 
@@ -108,6 +110,7 @@ extern "C" usl_status usl_init_indices(usl_ctx* c, int32_t* idx, uint64_t seed) 
     NEED(idx);
     USL_TRY(usl_prepare_device(c));
     c->csc_built_for = nullptr;
+    c->slot_order_for = nullptr;
     return usl_launch_init_indices(c, idx, seed);
 }
 
@@ -180,6 +183,7 @@ extern "C" usl_status usl_redistribute(usl_ctx* c, int32_t* idx, void* W, float*
     if (n == 0) return USL_OK;
     USL_TRY(usl_prepare_device(c));
     c->csc_built_for = nullptr;
+    c->slot_order_for = nullptr;
     return usl_launch_redistribute(c, idx, W, m1, m2, n, seed, epoch);
 }
 

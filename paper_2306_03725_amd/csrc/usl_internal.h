@@ -32,6 +32,9 @@ struct usl_ctx {
     uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by column
     int32_t* csc_label;       // [m*k] label j of that slot
     const int32_t* csc_built_for;  // idx pointer the lists were built from (NULL = stale)
+    // bank-aware order in which a label's slots are visited by the LDS gathers (performance only)
+    uint8_t* slot_order;           // [m*k] slot read at step s
+    const int32_t* slot_order_for; // idx pointer it was computed from (NULL = stale)
     float* gT;                size_t gT_cap;   // [m][bp] transposed upstream gradient
     float* gxT;               size_t gxT_cap;  // [d][bp] transposed input gradient
 };
@@ -60,6 +63,8 @@ usl_status usl_prepare_device(usl_ctx* ctx);
 // Grows *buf to at least `bytes` (old contents are dropped).
 usl_status usl_reserve(usl_ctx* ctx, void** buf, size_t* cap, size_t bytes);
 usl_status usl_check_launch(usl_ctx* ctx, const char* what);
+
+usl_status usl_build_slot_order(usl_ctx* ctx, const int32_t* idx);
 
 // Kernel launchers (one per file).  All take validated arguments.
 usl_status usl_launch_forward(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W,
