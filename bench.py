@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large", help="tiny | medium | large | large_wide | stress")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (FETCH+WRITE, scaled)")
     args = ap.parse_args()
@@ -141,6 +143,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:    # 2^30 bytes read + 2^30 bytes written by one elementwise kernel
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     events = []
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()

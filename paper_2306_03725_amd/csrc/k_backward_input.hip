@@ -1,13 +1,26 @@
 // Input gradient (Algorithm 2): grad_x[i][c] = sum over connections (j,t) with idx[j][t]==c of
 // W[j][t] * g[i][j].
 //
-// The paper scatters with one atomic add per (instance, connection).  On gfx950 neither global
-// nor LDS float atomics come near the needed rate (b*m*k additions), so the sum is turned into a
-// gather: a column-major view of the connectivity (for every feature c the list of its slots) is
-// rebuilt whenever idx changes, the upstream gradient is transposed to gT[m][b] so that the b
-// values of one label are contiguous, and one wavefront per (feature, tile of 256 instances) adds
-// W * gT rows in registers.  No atomics touch grad_x; the only non-determinism is the order of
-// the slots inside a column list (filled with an atomic cursor).
+// The paper scatters with one atomic add per (instance, connection).  On gfx950 neither global nor
+// LDS float atomics come near the needed rate (b*m*k additions), so the sum is turned into a gather
+// over a private column-major view of the connectivity, rebuilt whenever idx changes.
+//
+// Memory plan.  g is transposed to gT[m][b] so that the values of one label are contiguous.  The
+// naive gather (one wavefront per feature reading whole 1 KiB rows of gT) re-reads every row k
+// times from HBM / Infinity Cache (m*k*b*4 bytes: 16 GB at m=500k, k=32, b=256).  Instead:
+//   * the batch is cut into tiles of 32 instances (128-byte pieces of a gT row, one cache line),
+//     and the tile index is the fastest grid dimension, so that with round-robin dispatch of
+//     workgroups to the 8 XCDs all work on tile t lands on XCD t mod 8 and shares one L2;
+//   * the labels are cut into windows whose tile-slice of gT fits that L2; the kernel is launched
+//     once per window and handles the connections of every feature that fall into the window, so
+//     each 128-byte piece is fetched once and then served k times from L2;
+//   * the column lists are therefore grouped by (window, feature); partial sums are added into
+//     gxT[d][b] by the later windows (plain read-modify-write: launches are ordered).
+// Eight lanes (8 x float4 = 32 instances) form a group that walks one feature's list; a wavefront
+// reads eight 128-byte pieces per load instruction.  No atomics touch grad_x; the only
+// non-determinism is the order of the slots inside one (window, feature) list.
+#include <stdlib.h>
+
 #include "usl_internal.h"
 
 namespace {
@@ -18,47 +31,98 @@ __global__ void k_zero_u32(uint32_t* p, size_t n) {
     for (; i < n; i += s) p[i] = 0;
 }
 
+// bin of slot e: (window of its label) * d + its feature
 __global__ void __launch_bounds__(256)
-k_csc_count(const int32_t* __restrict__ idx, size_t N, uint32_t* __restrict__ count) {
-    const size_t s = (size_t)gridDim.x * 256;
-    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < N; e += s)
-        atomicAdd(&count[idx[e]], 1u);
-}
-
-// exclusive scan of count[d] into ptr[d+1]; cursor[c] = ptr[c].  One block.
-__global__ void __launch_bounds__(1024)
-k_csc_scan(uint32_t* __restrict__ cursor /* in: counts */, uint32_t* __restrict__ ptr, int d) {
-    __shared__ uint32_t part[1024];
-    const int per = (d + 1023) / 1024;
-    const int a = threadIdx.x * per, e = min(d, a + per);
-    uint32_t s = 0;
-    for (int q = a; q < e; ++q) s += cursor[q];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int q = 0; q < 1024; ++q) { const uint32_t v = part[q]; part[q] = run; run += v; }
-        ptr[d] = run;
-    }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (int q = a; q < e; ++q) {
-        const uint32_t v = cursor[q];
-        ptr[q] = run;
-        cursor[q] = run;
-        run += v;
-    }
-}
-
-__global__ void __launch_bounds__(256)
-k_csc_fill(const int32_t* __restrict__ idx, size_t N, int k, uint32_t* __restrict__ cursor,
-           uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
+k_csc_count(const int32_t* __restrict__ idx, size_t N, int k, int d, int win_labels,
+            uint32_t* __restrict__ count) {
     const size_t s = (size_t)gridDim.x * 256;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < N; e += s) {
-        const uint32_t pos = atomicAdd(&cursor[idx[e]], 1u);
-        slot[pos] = (uint32_t)e;
-        label[pos] = (int32_t)(e / (size_t)k);
+        const size_t j = e / (size_t)k;
+        atomicAdd(&count[(j / win_labels) * (size_t)d + idx[e]], 1u);
     }
+}
+
+// Exclusive scan of count[n] into ptr[n+1] (and cursor[c] = ptr[c]) in three launches: per-chunk
+// sums, a one-block scan of those, and a per-chunk rescan with the chunk's offset.
+constexpr int SCAN_NT = 1024, SCAN_PER = 8, SCAN_CHUNK = SCAN_NT * SCAN_PER;
+
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* sh, uint32_t* total) {
+    // sh: SCAN_NT words.  Returns the sum of v over lower thread ids; *total = sum over the block.
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 1; o < SCAN_NT; o <<= 1) {
+        const uint32_t t = threadIdx.x >= (unsigned)o ? sh[threadIdx.x - o] : 0u;
+        __syncthreads();
+        sh[threadIdx.x] += t;
+        __syncthreads();
+    }
+    *total = sh[SCAN_NT - 1];
+    return sh[threadIdx.x] - v;
+}
+
+__global__ void __launch_bounds__(SCAN_NT)
+k_scan_sums(const uint32_t* __restrict__ count, size_t n, uint32_t* __restrict__ sums) {
+    __shared__ uint32_t sh[SCAN_NT];
+    const size_t f0 = (size_t)blockIdx.x * SCAN_CHUNK + (size_t)threadIdx.x * SCAN_PER;
+    uint32_t s = 0;
+    for (int q = 0; q < SCAN_PER; ++q)
+        if (f0 + q < n) s += count[f0 + q];
+    uint32_t total;
+    block_exclusive_scan(s, sh, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(SCAN_NT)
+k_scan_top(uint32_t* __restrict__ sums, size_t nchunks, uint32_t* __restrict__ ptr_end) {
+    __shared__ uint32_t sh[SCAN_NT];
+    const size_t per = (nchunks + SCAN_NT - 1) / SCAN_NT;
+    const size_t a = min(nchunks, threadIdx.x * per), e = min(nchunks, a + per);
+    uint32_t s = 0;
+    for (size_t q = a; q < e; ++q) s += sums[q];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(s, sh, &total);
+    for (size_t q = a; q < e; ++q) { const uint32_t v = sums[q]; sums[q] = run; run += v; }
+    if (threadIdx.x == 0) *ptr_end = total;
+}
+
+__global__ void __launch_bounds__(SCAN_NT)
+k_scan_apply(uint32_t* __restrict__ cursor /* in: counts */, const uint32_t* __restrict__ sums,
+             size_t n, uint32_t* __restrict__ ptr) {
+    __shared__ uint32_t sh[SCAN_NT];
+    const size_t f0 = (size_t)blockIdx.x * SCAN_CHUNK + (size_t)threadIdx.x * SCAN_PER;
+    uint32_t v[SCAN_PER];
+    uint32_t s = 0;
+#pragma unroll
+    for (int q = 0; q < SCAN_PER; ++q) { v[q] = f0 + q < n ? cursor[f0 + q] : 0u; s += v[q]; }
+    uint32_t total;
+    uint32_t run = sums[blockIdx.x] + block_exclusive_scan(s, sh, &total);
+#pragma unroll
+    for (int q = 0; q < SCAN_PER; ++q) {
+        if (f0 + q < n) { ptr[f0 + q] = run; cursor[f0 + q] = run; }
+        run += v[q];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_csc_fill(const int32_t* __restrict__ idx, size_t N, int k, int d, int win_labels,
+           uint32_t* __restrict__ cursor, uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
+    const size_t s = (size_t)gridDim.x * 256;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < N; e += s) {
+        const size_t j = e / (size_t)k;
+        const uint32_t pos = atomicAdd(&cursor[(j / win_labels) * (size_t)d + idx[e]], 1u);
+        slot[pos] = (uint32_t)e;
+        label[pos] = (int32_t)j;
+    }
+}
+
+// weights in list order, as float32 (refreshed on every call: W changes with every Adam step)
+template <typename TS>
+__global__ void __launch_bounds__(256)
+k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, size_t N,
+           float* __restrict__ wl) {
+    const size_t s = (size_t)gridDim.x * 256;
+    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < N; p += s)
+        wl[p] = usl_load_f32<TS>(W, (size_t)slot[p]);
 }
 
 // out[c][r] = in[r][c] for r < R, c < C; rows of in / out are ld_in / ld_out elements apart.
@@ -81,65 +145,100 @@ k_transpose(const float* __restrict__ in, float* __restrict__ out, int64_t R, in
     }
 }
 
-// One wavefront per (feature c, tile of 256 instances); lane l owns instances 4l .. 4l+3 of the tile.
-template <typename TS>
+// One launch per label window: launch boundaries are what keeps all workgroups of an XCD inside the
+// same window (a single persistent sweep, with or without a soft pacing counter, drifted apart and
+// lost the L2 reuse -- measured slower).  blockIdx.x = tile of 32 instances (fastest, so that a
+// tile stays on one XCD), blockIdx.y = block of 32 features; lanes 8g..8g+7 of a wavefront walk the
+// list of one feature, lane l of the group owns instances 4l..4l+3 of the tile.
 __global__ void __launch_bounds__(256)
-k_bwd_input_gather(const float* __restrict__ gT, const TS* __restrict__ W,
-                   const uint32_t* __restrict__ ptr, const uint32_t* __restrict__ slot,
-                   const int32_t* __restrict__ label, float* __restrict__ gxT, int d, int bp) {
-    const int lane = threadIdx.x & 63;
-    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (c >= d) return;  // whole wavefront leaves together
-    const int i0 = blockIdx.y * 256 + lane * 4;
-    const bool live = i0 < bp;
-    const uint32_t p0 = ptr[c], p1 = ptr[c + 1];
+k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
+                   const uint32_t* __restrict__ ptr /* this window's d+1 offsets */,
+                   const int32_t* __restrict__ label, float* __restrict__ gxT, int d, int bp,
+                   int accumulate) {
+    const int c = blockIdx.y * 32 + (threadIdx.x >> 3);
+    const int i0 = blockIdx.x * 32 + (threadIdx.x & 7) * 4;
+    if (c >= d || i0 >= bp) return;
+    uint32_t p = ptr[c];
+    const uint32_t p1 = ptr[c + 1];
+    const float* col = gT + i0;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (uint32_t base = p0; base < p1; base += 64) {
-        const int n = (int)min(64u, p1 - base);
-        int32_t jv = 0;
-        float wv = 0.f;
-        if (lane < n) {
-            jv = label[base + lane];
-            wv = usl_load_f32<TS>(W, (size_t)slot[base + lane]);
+    for (; p + 4 <= p1; p += 4) {
+        int32_t j[4];
+        float w[4];
+        float4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {   // the 8 lanes of a group read the same entry; the next ones hit L1
+            j[q] = label[p + q];
+            w[q] = wl[p + q];
         }
-        // lanes >= n hold label 0 and weight 0, so the count can be rounded up to the unroll
-        // factor: the extra rows are valid memory and contribute nothing
-        for (int u0 = 0; u0 < n; u0 += 8) {
-            float4 v[8];
-            float w[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int32_t j = __builtin_amdgcn_readlane(jv, u0 + q);
-                w[q] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wv), u0 + q));
-                v[q] = live ? *reinterpret_cast<const float4*>(gT + (size_t)j * bp + i0)
-                            : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+        for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * bp);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                acc.x = fmaf(w[q], v[q].x, acc.x); acc.y = fmaf(w[q], v[q].y, acc.y);
-                acc.z = fmaf(w[q], v[q].z, acc.z); acc.w = fmaf(w[q], v[q].w, acc.w);
-            }
+        for (int q = 0; q < 4; ++q) {
+            acc.x = fmaf(w[q], v[q].x, acc.x); acc.y = fmaf(w[q], v[q].y, acc.y);
+            acc.z = fmaf(w[q], v[q].z, acc.z); acc.w = fmaf(w[q], v[q].w, acc.w);
         }
     }
-    if (live) *reinterpret_cast<float4*>(gxT + (size_t)c * bp + i0) = acc;
+    for (; p < p1; ++p) {
+        const float w = wl[p];
+        const float4 v = *reinterpret_cast<const float4*>(col + (size_t)label[p] * bp);
+        acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
+        acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
+    }
+    float4* dst = reinterpret_cast<float4*>(gxT + (size_t)c * bp + i0);
+    if (accumulate) {
+        const float4 o = *dst;
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+    }
+    *dst = acc;
+}
+
+int window_labels(const usl_ctx* c) {
+    // a window's 128-byte-per-label slice of gT should sit in one XCD's 4 MiB L2 with room to spare
+    int w = 16384;
+    const char* e = getenv("USL_TUNE_WIN");
+    if (e && atoi(e) > 0) w = atoi(e);
+    return w;
 }
 
 usl_status build_csc(usl_ctx* c, const int32_t* idx) {
     const size_t N = (size_t)c->m * c->k;
-    if (!c->csc_ptr) {
-        size_t cap = 0;
-        USL_TRY(usl_reserve(c, (void**)&c->csc_ptr, &cap, ((size_t)c->d + 1) * 4)); cap = 0;
-        USL_TRY(usl_reserve(c, (void**)&c->csc_cursor, &cap, (size_t)c->d * 4)); cap = 0;
-        USL_TRY(usl_reserve(c, (void**)&c->csc_slot, &cap, N * 4)); cap = 0;
-        USL_TRY(usl_reserve(c, (void**)&c->csc_label, &cap, N * 4));
+    const int wl = window_labels(c);
+    const size_t nwin = ((size_t)c->m + wl - 1) / wl;
+    const size_t nbins = nwin * (size_t)c->d;
+    if (nbins + 1 > (size_t)0xFFFFFFF0u) USL_FAIL(c, USL_ESHAPE, "too many (window, feature) lists");
+    if (!c->csc_ptr || c->csc_win_labels != wl) {
+        size_t cap = c->csc_ptr_cap;
+        USL_TRY(usl_reserve(c, (void**)&c->csc_ptr, &cap, (nbins + 1) * 4));
+        c->csc_ptr_cap = cap; cap = c->csc_cursor_cap;
+        USL_TRY(usl_reserve(c, (void**)&c->csc_cursor, &cap, nbins * 4));
+        c->csc_cursor_cap = cap;
+        if (!c->csc_slot) {
+            cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_slot, &cap, N * 4));
+            cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_label, &cap, N * 4));
+            cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_w, &cap, N * 4));
+        }
+        c->csc_win_labels = wl;
     }
     size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
     if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
-    hipLaunchKernelGGL(k_zero_u32, dim3(64), dim3(256), 0, c->stream, c->csc_cursor, (size_t)c->d);
-    hipLaunchKernelGGL(k_csc_count, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx, N, c->csc_cursor);
-    hipLaunchKernelGGL(k_csc_scan, dim3(1), dim3(1024), 0, c->stream, c->csc_cursor, c->csc_ptr, c->d);
+    hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
+    hipLaunchKernelGGL(k_csc_count, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx, N, c->k,
+                       c->d, wl, c->csc_cursor);
+    const size_t nchunks = (nbins + SCAN_CHUNK - 1) / SCAN_CHUNK;
+    {
+        size_t cap = c->tie_counts_cap;  // the redistribution's block-count buffer doubles as scan scratch
+        USL_TRY(usl_reserve(c, (void**)&c->tie_counts, &cap, nchunks * 4));
+        c->tie_counts_cap = cap;
+    }
+    hipLaunchKernelGGL(k_scan_sums, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, c->csc_cursor,
+                       nbins, c->tie_counts);
+    hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(SCAN_NT), 0, c->stream, c->tie_counts, nchunks,
+                       c->csc_ptr + nbins);
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, c->csc_cursor,
+                       c->tie_counts, nbins, c->csc_ptr);
     hipLaunchKernelGGL(k_csc_fill, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx, N, c->k,
-                       c->csc_cursor, c->csc_slot, c->csc_label);
+                       c->d, wl, c->csc_cursor, c->csc_slot, c->csc_label);
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
     return USL_OK;
@@ -149,22 +248,34 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
 
 usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
                                      float* grad_x, int32_t b) {
-    if (c->csc_built_for != idx) USL_TRY(build_csc(c, idx));
+    if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) USL_TRY(build_csc(c, idx));
+    const size_t N = (size_t)c->m * c->k;
     const int bp = (b + 3) & ~3;
+    const int wl = c->csc_win_labels;
+    const int nwin = (int)((c->m + wl - 1) / wl);
     USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)c->m * bp * 4));
     USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)c->d * bp * 4));
+    {   // weights in list order
+        size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
+        if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
+        if (c->storage == USL_F32)
+            hipLaunchKernelGGL(k_gather_w<float>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
+                               (const float*)W, c->csc_slot, N, c->csc_w);
+        else
+            hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
+                               (const uint16_t*)W, c->csc_slot, N, c->csc_w);
+    }
     {   // gT[m][bp] = transpose of g[b][m]
         dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));
-        hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m, c->m, (int64_t)bp);
+        hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
+                           c->m, (int64_t)bp);
     }
     {
-        dim3 grid((unsigned)((c->d + 3) / 4), (unsigned)((bp + 255) / 256));
-        if (c->storage == USL_F32)
-            hipLaunchKernelGGL(k_bwd_input_gather<float>, grid, dim3(256), 0, c->stream, c->gT,
-                               (const float*)W, c->csc_ptr, c->csc_slot, c->csc_label, c->gxT, c->d, bp);
-        else
-            hipLaunchKernelGGL(k_bwd_input_gather<uint16_t>, grid, dim3(256), 0, c->stream, c->gT,
-                               (const uint16_t*)W, c->csc_ptr, c->csc_slot, c->csc_label, c->gxT, c->d, bp);
+        dim3 grid((unsigned)((bp + 31) / 32), (unsigned)((c->d + 31) / 32));
+        for (int w = 0; w < nwin; ++w)
+            hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d, bp,
+                               w > 0 ? 1 : 0);
     }
     {   // grad_x[b][d] = transpose of gxT[d][bp] (first b columns)
         dim3 grid((unsigned)((b + 31) / 32), (unsigned)((c->d + 31) / 32));

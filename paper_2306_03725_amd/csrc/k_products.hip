@@ -8,6 +8,8 @@
 // 16-byte loads, and every gather is an LDS read.  idx and W therefore leave HBM once per
 // workgroup, x is re-read once per label block (it stays in L2 / Infinity Cache), and out /
 // grad_W are written with coalesced stores.
+#include <stdlib.h>
+
 #include "usl_internal.h"
 
 namespace {
@@ -161,6 +163,7 @@ struct TileGeom {
     int nparts;         // slices per row
     int inst_per_group; // instances handled by one blockIdx.y
     int vec_ok;         // 16-byte copies allowed
+    int dbg;
 };
 
 // ---------------------------------------------------------------------------- forward
@@ -220,8 +223,9 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                 const int c0 = part * tg.part_cols;
                 const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
                 __syncthreads();
-                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+                if (!(tg.dbg & 1) || i == i_begin) stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
+                if (tg.dbg & 2) continue;
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     keep_packed(pk[l]);
@@ -407,6 +411,7 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     TileGeom tg;
     const size_t row_bytes = (size_t)c->d * esize;
     tg.vec_ok = (row_bytes % 16 == 0) && (((uintptr_t)x) % 16 == 0);
+    tg.dbg = getenv("USL_DBG") ? atoi(getenv("USL_DBG")) : 0;
     if (row_bytes <= (size_t)USL_ROW_LDS_BYTES) {
         tg.nparts = 1;
         tg.part_cols = c->d;
@@ -551,7 +556,9 @@ usl_status forward_t(usl_ctx* c, const void* x, const int32_t* idx, const void* 
     switch (c->k) {
         case 8:  return big ? run_forward<8, 16, 512, TS>(c, x, idx, W, out, b) : run_forward<8, 1, 256, TS>(c, x, idx, W, out, b);
         case 16: return big ? run_forward<16, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<16, 1, 256, TS>(c, x, idx, W, out, b);
-        case 32: return big ? run_forward<32, 4, 512, TS>(c, x, idx, W, out, b) : run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
+        case 32:
+            if (big && getenv("USL_TUNE_NT1024")) return run_forward<32, 2, 1024, TS>(c, x, idx, W, out, b);
+            return big ? run_forward<32, 4, 512, TS>(c, x, idx, W, out, b) : run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
         default: return big ? run_forward<64, 2, 512, TS>(c, x, idx, W, out, b) : run_forward<64, 1, 256, TS>(c, x, idx, W, out, b);
     }
 }
@@ -565,7 +572,9 @@ usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const in
     switch (c->k) {
         case 8:  return big ? run_backward_weight<8, 16, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b);
         case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b);
-        case 32: return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        case 32:
+            if (big && getenv("USL_TUNE_NT1024")) return run_backward_weight<32, 2, 1024, TS>(c, g, x, idx, grad_W, b);
+            return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b);
         default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b);
     }
 }

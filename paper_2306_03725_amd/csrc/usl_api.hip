@@ -29,7 +29,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (!c) return USL_OK;
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
-                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->gT, c->gxT,
+                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->csc_w, c->gT, c->gxT,
                         c->slot_order};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)

@@ -27,10 +27,12 @@ struct usl_ctx {
     uint32_t* tie_counts;     size_t tie_counts_cap;
     int64_t* counter64;       // small device counter (validate)
     // transposed (column-major) connectivity for backward_input
-    uint32_t* csc_ptr;        // [d+1] start of each column's list
-    uint32_t* csc_cursor;     // [d]
-    uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by column
+    uint32_t* csc_ptr;        size_t csc_ptr_cap;     // [nwin*d+1] start of each (window, feature) list
+    uint32_t* csc_cursor;     size_t csc_cursor_cap;  // [nwin*d]
+    uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by (label window, feature)
     int32_t* csc_label;       // [m*k] label j of that slot
+    float* csc_w;             // [m*k] W of that slot (refreshed by every backward_input)
+    int csc_win_labels;       // labels per window the lists were built with
     const int32_t* csc_built_for;  // idx pointer the lists were built from (NULL = stale)
     // bank-aware order in which a label's slots are visited by the LDS gathers (performance only)
     uint8_t* slot_order;           // [m*k] slot read at step s
