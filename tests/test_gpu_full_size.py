@@ -1,0 +1,125 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times.  The oracle cannot recompute 1e8..3e9 outputs in seconds, so each call is checked on sampled
+outputs it can compute one by one (all labels for a few instances, all instances for a few thousand
+labels), teacher-forced on the GPU's own state; redistribution is checked in full."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    hp = wl.ADAM
+    print("full-size", cfg.name, m, d, k, b, cfg.storage, flush=True)
+    r = wl.rng(cfg, 17)
+    J = np.sort(r.choice(m, size=n_lab, replace=False))
+    I = np.sort(r.choice(b, size=n_inst, replace=False))
+    dJ, dI = torch.from_numpy(J).cuda(), torch.from_numpy(I).cuda()
+    L = usl.Layer(m, d, k, b, cfg.storage)
+    # state: connectivity from the library's own init (checked against the oracle in full)
+    d_idx = gu.empty((m, k), torch.int32)
+    L.init_indices(d_idx, 1000 * cfg.index)
+    idx = gu.host(d_idx)
+    np.testing.assert_array_equal(idx, orc.init_indices(m, d, k, 1000 * cfg.index))
+    W = wl.gen_W(cfg)
+    x = wl.gen_x(cfg)
+    off, lab = wl.gen_targets(cfg)
+    d_W, d_x = gu.dev(W), gu.dev(x)
+    out = gu.empty((b, m))
+    loss = gu.empty((1,))
+    scale = float(np.float32(1.0 / b))
+    # forward
+    L.forward(d_x, d_idx, d_W, out, b)
+    out_I = gu.host(out.index_select(0, dI))                  # [n_inst, m]
+    out_J = gu.host(out.index_select(1, dJ).contiguous())     # [b, n_lab]
+    assert_close(out_I, orc.forward(np.ascontiguousarray(x[I]), idx, W), 1e-5, "out rows")
+    assert_close(out_J, orc.forward(x, np.ascontiguousarray(idx[J]), np.ascontiguousarray(W[J])), 1e-5, "out cols")
+    print("forward ok", flush=True)
+    # BCE in place
+    h_out = gu.host(out) if full_loss else None
+    L.bce_loss_grad(out, gu.dev(off), gu.dev(lab), scale, out, loss, b)
+    sub_off = np.zeros(n_inst + 1, np.int64)
+    sub_lab = []
+    for q, i in enumerate(I):
+        sub_lab.extend(lab[off[i]:off[i + 1]])
+        sub_off[q + 1] = len(sub_lab)
+    _, ref_g_I = orc.bce_loss_grad(out_I, sub_off, np.array(sub_lab, np.int32), scale)
+    g_I = gu.host(out.index_select(0, dI))
+    assert_close(g_I, ref_g_I, 1e-5, "g rows")
+    if full_loss:
+        ref_loss, ref_g = orc.bce_loss_grad(h_out, off, lab, scale)
+        assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+        g_J = gu.host(out.index_select(1, dJ).contiguous())
+        assert_close(g_J, np.ascontiguousarray(ref_g[:, J]), 1e-5, "g cols")
+        del ref_g, h_out
+    else:
+        g_J = gu.host(out.index_select(1, dJ).contiguous())
+        assert np.isfinite(loss.item())
+    print("bce ok", flush=True)
+    # backward products on the GPU's own g
+    gW, gx = gu.empty((m, k)), gu.empty((b, d))
+    L.backward_weight(out, d_x, d_idx, gW, b)
+    L.backward_input(out, d_idx, d_W, gx, b)
+    gW_J = gu.host(gW.index_select(0, dJ))
+    assert_close(gW_J, orc.backward_weight(g_J, x, np.ascontiguousarray(idx[J])), 1e-5, "grad_W rows")
+    assert_close(gu.host(gx.index_select(0, dI)), orc.backward_input(g_I, idx, W, d), 1e-4, "grad_x rows")
+    print("backward ok", flush=True)
+    # Adam on sampled rows
+    d_m1, d_m2 = gu.dev(np.zeros((m, k), np.float32)), gu.dev(np.zeros((m, k), np.float32))
+    for t in (1, 2):
+        W_J = gu.host(d_W.index_select(0, dJ)).copy()
+        m1_J, m2_J = gu.host(d_m1.index_select(0, dJ)).copy(), gu.host(d_m2.index_select(0, dJ)).copy()
+        L.adam_step(d_W, gW, d_m1, d_m2, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        pre = orc.adam_step(W_J, gW_J, m1_J, m2_J, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+        assert_close(gu.host(d_m1.index_select(0, dJ)), m1_J, 1e-4, "m1")
+        assert_close(gu.host(d_m2.index_select(0, dJ)), m2_J, 1e-4, "m2")
+        got = gu.host(d_W.index_select(0, dJ))
+        if cfg.storage == "f32":
+            assert_close(got, W_J, 1e-4, "W")
+        else:
+            got = wl.bf16_bits_to_f32(got).astype(np.float64)
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(pre), 1e-30))) - 7)
+            rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))   # same guard as assert_close
+            assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre) + 1e-4 * rms).all()
+    print("adam ok", flush=True)
+    # redistribution, in full
+    h_idx, h_W, h_m1, h_m2 = (gu.host(t).copy() for t in (d_idx, d_W, d_m1, d_m2))
+    seed = wl.redistribution_seed(cfg)
+    n = L.redistribute(d_idx, d_W, d_m1, d_m2, cfg.fraction, seed, 0)
+    n_ref, _ = orc.redistribute(h_idx, h_W, h_m1, h_m2, d, cfg.fraction, seed, 0)
+    assert n == n_ref
+    np.testing.assert_array_equal(gu.host(d_idx), h_idx)
+    np.testing.assert_array_equal(gu.host(d_W).view(np.uint8), h_W.view(np.uint8))
+    np.testing.assert_array_equal(gu.host(d_m1), h_m1)
+    np.testing.assert_array_equal(gu.host(d_m2), h_m2)
+    assert L.validate_indices(d_idx) == 0
+    # the products follow the new connectivity (private layouts are rebuilt)
+    L.forward(d_x, d_idx, d_W, out, b)
+    assert_close(gu.host(out.index_select(0, dI)), orc.forward(np.ascontiguousarray(x[I]), h_idx, h_W), 1e-5,
+                 "out rows after redistribution")
+    L.backward_input(out, d_idx, d_W, gx, b)
+    assert_close(gu.host(gx.index_select(0, dI)),
+                 orc.backward_input(gu.host(out.index_select(0, dI)), h_idx, h_W, d), 1e-4,
+                 "grad_x rows after redistribution")
+    print("redistribute ok", flush=True)
+    L.close()
+    torch.cuda.empty_cache()
+
+
+def test_large_full_size(orc):
+    run_full(wl.CONFIGS["large"], orc, full_loss=True)
+
+
+def test_large_wide_full_size(orc):
+    run_full(wl.CONFIGS["large_wide"], orc, full_loss=False, n_lab=2048)
+
+
+def test_stress_full_size(orc):
+    run_full(wl.CONFIGS["stress"], orc, full_loss=False, n_lab=1024, n_inst=2)
