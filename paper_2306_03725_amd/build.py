@@ -26,7 +26,7 @@ def build(force=True, verbose=False):
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
-    deps = [os.path.join(CSRC, "usl_internal.h"), os.path.join(HERE, "..", "include", "usl.h")]
+    deps = [os.path.join(CSRC, "usl_internal.h"), os.path.join(CSRC, "k_products_common.h"), os.path.join(HERE, "..", "include", "usl.h")]
     newest_dep = max(os.path.getmtime(p) for p in deps)
     for src in SOURCES:
         sp = os.path.join(CSRC, src)
