@@ -37,7 +37,6 @@ struct TileGeom {
     int nparts;         // slices per row
     int inst_per_group; // instances handled by one blockIdx.y
     int vec_ok;         // 16-byte copies allowed
-    int dbg;
 };
 
 // ---------------------------------------------------------------------------- forward
@@ -86,6 +85,9 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
             }
         }
     } else {
+        // The scores of an instance are written while the next instance's row is being gathered: a
+        // store issued right before the next staging would make its vmcnt(0) wait for the store too.
+        float prev[LPT];
 #pragma unroll 1
         for (int i = i_begin; i < i_end; ++i) {
             float acc[LPT];
@@ -97,10 +99,14 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                 const int c0 = part * tg.part_cols;
                 const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
                 __syncthreads();
-                if (!(tg.dbg & 1) || i == i_begin) stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end && !(tg.dbg & 8)) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
-                if (tg.dbg & 2) continue;
+                if (part == 0 && i > i_begin) {
+#pragma unroll
+                    for (int l = 0; l < LPT; ++l)
+                        if (jme + (int64_t)l * NT < m) out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
+                }
+                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     keep_packed(pk[l]);
@@ -113,13 +119,17 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                     }
                     // finish the sum here; left alone the compiler sinks the multiply-adds into
-                    // the guarded store below and keeps every gathered value alive until then
+                    // the guarded store and keeps every gathered value alive until then
                     asm volatile("" : "+v"(acc[l]));
                 }
             }
 #pragma unroll
+            for (int l = 0; l < LPT; ++l) prev[l] = acc[l];
+        }
+        if (i_end > i_begin) {
+#pragma unroll
             for (int l = 0; l < LPT; ++l)
-                if (jme + (int64_t)l * NT < m && !(tg.dbg & 4)) out[(size_t)i * m + jme + (int64_t)l * NT] = acc[l];
+                if (jme + (int64_t)l * NT < m) out[(size_t)(i_end - 1) * m + jme + (int64_t)l * NT] = prev[l];
         }
     }
 }
@@ -213,7 +223,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 __syncthreads();
                 stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end && !(tg.dbg & 8)) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
+                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     keep_packed(pk[l]);
@@ -287,7 +297,6 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     TileGeom tg;
     const size_t row_bytes = (size_t)c->d * esize;
     tg.vec_ok = (row_bytes % 16 == 0) && (((uintptr_t)x) % 16 == 0);
-    tg.dbg = getenv("USL_DBG") ? atoi(getenv("USL_DBG")) : 0;
     if (row_bytes <= (size_t)USL_ROW_LDS_BYTES) {
         tg.nparts = 1;
         tg.part_cols = c->d;
@@ -430,10 +439,9 @@ usl_status forward_t(usl_ctx* c, const void* x, const int32_t* idx, const void* 
     if (!fast_path_ok(c, idx, W)) return run_forward_generic<TS>(c, x, idx, W, out, b);
     const bool big = c->m >= (int64_t)c->num_cu * 1024;
     switch (c->k) {
-        case 8:  return big ? run_forward<8, 16, 512, TS>(c, x, idx, W, out, b) : run_forward<8, 1, 256, TS>(c, x, idx, W, out, b);
+        case 8:  return big ? run_forward<8, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<8, 1, 256, TS>(c, x, idx, W, out, b);
         case 16: return big ? run_forward<16, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<16, 1, 256, TS>(c, x, idx, W, out, b);
         case 32:
-            if (big && getenv("USL_TUNE_NT1024")) return run_forward<32, 2, 1024, TS>(c, x, idx, W, out, b);
             return big ? run_forward<32, 4, 512, TS>(c, x, idx, W, out, b) : run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
         default: return big ? run_forward<64, 2, 512, TS>(c, x, idx, W, out, b) : run_forward<64, 1, 256, TS>(c, x, idx, W, out, b);
     }
@@ -446,10 +454,9 @@ usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const in
         return run_backward_weight_generic<TS>(c, g, x, idx, grad_W, b);
     const bool big = c->m >= (int64_t)c->num_cu * 1024;
     switch (c->k) {
-        case 8:  return big ? run_backward_weight<8, 16, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        case 8:  return big ? run_backward_weight<8, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b);
         case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b);
         case 32:
-            if (big && getenv("USL_TUNE_NT1024")) return run_backward_weight<32, 2, 1024, TS>(c, g, x, idx, grad_W, b);
             return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b);
         default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b);
     }

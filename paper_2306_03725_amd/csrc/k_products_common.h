@@ -125,20 +125,30 @@ __device__ __forceinline__ void fetch_w(const float* __restrict__ W, int64_t row
 #pragma unroll
     for (int t = 0; t < K; ++t) w[t] = valid ? __uint_as_float(p[so.at(t)]) : 0.f;
 }
+// bfloat16 rows are widened to float32 words on their way into the transposition buffer, so the
+// per-lane part is the same as for float32.
 template <int K, int NT>
 __device__ __forceinline__ void fetch_w(const uint16_t* __restrict__ W, int64_t row0, int64_t m,
                                         uint32_t* lds, const SlotOrder<K>& so, float (&w)[K]) {
     __syncthreads();
-    rows_to_lds<K / 2, NT>(reinterpret_cast<const uint32_t*>(W), row0, m, lds);
+    {
+        int64_t nvalid = m - row0;
+        nvalid = nvalid < 0 ? 0 : (nvalid > NT ? NT : nvalid);
+        const int nv = (int)(nvalid * K / 8);
+        const uint4* s = reinterpret_cast<const uint4*>(W + row0 * K);
+        for (int v = threadIdx.x; v < nv; v += NT) {
+            const uint4 q = s[v];
+            const int f = v * 8, r = f / K, t = f % K;
+            uint32_t* p = lds + r * (K + 1) + t;
+            p[0] = q.x << 16; p[1] = q.x & 0xFFFF0000u; p[2] = q.y << 16; p[3] = q.y & 0xFFFF0000u;
+            p[4] = q.z << 16; p[5] = q.z & 0xFFFF0000u; p[6] = q.w << 16; p[7] = q.w & 0xFFFF0000u;
+        }
+    }
     __syncthreads();
     const bool valid = row0 + threadIdx.x < m;
-    const uint32_t* p = lds + threadIdx.x * (K / 2 + 1);
+    const uint32_t* p = lds + threadIdx.x * (K + 1);
 #pragma unroll
-    for (int t = 0; t < K; ++t) {
-        const int slot = so.at(t);
-        const uint32_t u = valid ? p[slot >> 1] : 0u;
-        w[t] = __uint_as_float((slot & 1) ? (u & 0xFFFF0000u) : (u << 16));
-    }
+    for (int t = 0; t < K; ++t) w[t] = valid ? __uint_as_float(p[so.at(t)]) : 0.f;
 }
 
 // Stops the compiler from hoisting the unpacked indices out of the instance loop: unpacking is two
