@@ -61,7 +61,15 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
         fetch_idx_packed<K, NT>(idx, row0, m, reinterpret_cast<uint32_t*>(lds_raw), so, pk[l]);
         fetch_w<K, NT>(W, row0, m, reinterpret_cast<uint32_t*>(lds_raw), so, w[l]);
     }
-    const int64_t jme = j0 + threadIdx.x;  // label of slot l is jme + l*NT
+    const int64_t jme = j0 + threadIdx.x;
+    // 32 words of zeros (one per bank) behind the slice buffer, for the masked gathers of MODE 1
+    const uint32_t zcol = (uint32_t)tg.part_cols + (uint32_t)(threadIdx.x & 31) * (4 / sizeof(TS));
+    if (MODE == 1) {
+        __syncthreads();
+        if (threadIdx.x < 32)
+            reinterpret_cast<uint32_t*>(lds_raw)[(size_t)tg.part_cols * sizeof(TS) / 4 + threadIdx.x] = 0u;
+    }
+  // label of slot l is jme + l*NT
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
     if (MODE == 2) {
@@ -113,7 +121,10 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
                         const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
-                        if (MODE == 0 || c < cols) acc[l] = fmaf(w[l][t], lds_val(lds, c), acc[l]);
+                        // sliced rows: a slot outside the slice reads a word of zeros behind it
+                        // (no branch, so the gathers stay pipelined)
+                        const uint32_t cc = (MODE == 0 || c < cols) ? c : zcol;
+                        acc[l] = fmaf(w[l][t], lds_val(lds, cc), acc[l]);
                         // a few gathers in flight at a time: their results would otherwise
                         // crowd out the resident indices and weights
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
@@ -184,6 +195,14 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
         for (int t = 0; t < K; ++t) acc[l][t] = 0.f;
     }
     const int64_t jme = j0 + threadIdx.x;
+    // 32 words of zeros (one per bank) behind the slice buffer, for the masked gathers of MODE 1
+    const uint32_t zcol = (uint32_t)tg.part_cols + (uint32_t)(threadIdx.x & 31) * (4 / sizeof(TS));
+    if (MODE == 1) {
+        __syncthreads();
+        if (threadIdx.x < 32)
+            reinterpret_cast<uint32_t*>(lds_raw)[(size_t)tg.part_cols * sizeof(TS) / 4 + threadIdx.x] = 0u;
+    }
+
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
     if (MODE == 2) {
@@ -230,7 +249,8 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
                         const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
-                        if (MODE == 0 || c < cols) acc[l][t] = fmaf(gv[l], lds_val(lds, c), acc[l][t]);
+                        const uint32_t cc = (MODE == 0 || c < cols) ? c : zcol;
+                        acc[l][t] = fmaf(gv[l], lds_val(lds, cc), acc[l][t]);
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -321,7 +341,7 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     G = (b + tg.inst_per_group - 1) / tg.inst_per_group;
     *groups = G;
     *lds_bytes = tg.nparts == 1 ? (size_t)tg.rows_per_tile * row_bytes
-                                : (size_t)tg.part_cols * esize;
+                                : (size_t)tg.part_cols * esize + 128;   // + the zero words
     return tg;
 }
 
