@@ -19,6 +19,20 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 
+# HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the
+# same counters read for a plain copy of known size); summary and commands in
+# profiles/train_step_large_f32_hbm_bytes.txt.  Only the workload it was measured on has an entry.
+MEASURED_TRAFFIC_BYTES = {
+    "large": {"backward_input": 6204151 * 1024, "forward": 903564 * 1024, "backward_weight": 918966 * 1024},
+}
+KERNELS_OF_CALL = {
+    "forward": "k_forward (1 launch)",
+    "bce": "k_bce + k_bce_finish",
+    "backward_weight": "k_backward_weight (1 launch)",
+    "backward_input": "k_gather_w + k_transpose + one k_bwd_input_window per label window + k_transpose",
+    "adam": "k_adam (1 launch)",
+}
+
 
 def algorithmic_bytes(cfg):
     """Bytes each call has to move at the C-ABI level (x counted once per pass)."""
@@ -174,10 +188,16 @@ def main():
     # the dominant call and its roofline position (algorithmic bytes / measured time)
     dom = max((c for c in calls[:5]), key=lambda c: call_ms[c] or 0.0)
     dom_gbps = ab[dom] / (call_ms[dom] * 1e-3) / 1e9
-    roof = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom)
+    if args.traffic_kib is not None:
+        traffic = args.traffic_kib * 1024
+    roof = {"bound": "hbm", "kernel": "usl_%s: %s" % (dom, KERNELS_OF_CALL[dom]),
+            "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
             "ms_per_launch": round(call_ms[dom], 4), "algorithmic_bytes": ab[dom],
-            "traffic": (args.traffic_kib * 1024 if args.traffic_kib is not None else None)}
+            "traffic": traffic,
+            "note": "dominant call of the step; achieved = algorithmic bytes / HIP-event time of the call; "
+                    "traffic = HBM bytes per call from rocprofv3 counters (profiles/), measured offline"}
     step_gbps = ab["step"] / (ms_per_step * 1e-3) / 1e9
     res = {
         "metric": "sparse_layer_train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s",
