@@ -112,6 +112,17 @@ def bce_loss_grad(out, tgt_off, tgt_lab, scale):
     return loss.value, g
 
 
+def sqh_loss_grad(out, tgt_off, tgt_lab, scale):
+    """Sparse-target squared hinge summed over labels; returns (loss (double), g)."""
+    _chk(out, np.float32), _chk(tgt_off, np.int64), _chk(tgt_lab, np.int32)
+    b, m = out.shape
+    g = np.empty_like(out)
+    loss = ctypes.c_double(0.0)
+    lib().orc_sqh_loss_grad(_p(out), _p(tgt_off), _p(tgt_lab), ctypes.c_float(scale), _p(g),
+                            ctypes.byref(loss), ctypes.c_int64(m), ctypes.c_int32(b))
+    return loss.value, g
+
+
 def adam_step(W, grad_W, m1, m2, t, lr, beta1, beta2, eps):
     """In-place Adam on W, m1, m2.  For bfloat16 W returns the unrounded float32 values."""
     _chk(W), _chk(grad_W, np.float32), _chk(m1, np.float32), _chk(m2, np.float32)

@@ -120,6 +120,31 @@ void orc_bce_loss_grad(const float* out, const int64_t* tgt_off, const int32_t* 
     *loss_out = (double)scale * total;
 }
 
+/* One-vs-all squared hinge loss, the loss the paper mainly uses (Section 3.3):
+ *   l(y, z) = max(0, 1 - y*z)^2 with y = +1 for listed labels and -1 otherwise,
+ *   dl/dz = -2*y*max(0, 1 - y*z), exactly zero whenever y*z >= 1.
+ * loss = scale * sum_{i,j} l,  g = scale * dl/dz.  g may be the same array as out. */
+void orc_sqh_loss_grad(const float* out, const int64_t* tgt_off, const int32_t* tgt_lab,
+                       float scale, float* g, double* loss_out, int64_t m, int32_t b) {
+    double total = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : total)
+    for (int32_t i = 0; i < b; ++i) {
+        uint8_t* y = (uint8_t*)calloc((size_t)m, 1);
+        for (int64_t p = tgt_off[i]; p < tgt_off[i + 1]; ++p) y[tgt_lab[p]] = 1;
+        double acc = 0.0;
+        for (int64_t j = 0; j < m; ++j) {
+            double z = (double)out[(int64_t)i * m + j];
+            double yy = y[j] ? 1.0 : -1.0;
+            double margin = fmax(0.0, 1.0 - yy * z);
+            acc += margin * margin;
+            g[(int64_t)i * m + j] = (float)((double)scale * (-2.0 * yy * margin));
+        }
+        free(y);
+        total += acc;
+    }
+    *loss_out = (double)scale * total;
+}
+
 /* Adam (Kingma & Ba, Algorithm 1; the optimizer named in Section 4.1) on the m*k values.
  * t is the 1-based step count.  With storage==1, W is bfloat16: the updated value is
  * rounded float -> bfloat16 (nearest even) and, if W_f32_out is not NULL, the unrounded

@@ -133,6 +133,39 @@ def test_bce_gradient_is_derivative_of_loss(orc):
         assert abs((lp - lm) / (2 * h) - g[i, j]) < 2e-5
 
 
+# ---------------------------------------------------------------- squared hinge
+def test_sqh_closed_forms(orc):
+    """Section 3.3: l = max(0, 1 - y z)^2, gradient -2 y max(0, 1 - y z), zero iff y z >= 1."""
+    out = np.array([[2.0, 1.0, 0.5, 0.0, -0.5, -1.0, -3.0],
+                    [2.0, 1.0, 0.5, 0.0, -0.5, -1.0, -3.0]], np.float32)
+    off = np.array([0, 7, 7], np.int64)          # instance 0: every label positive; instance 1: none
+    lab = np.arange(7, dtype=np.int32)
+    loss, g = orc.sqh_loss_grad(out, off, lab, 0.5)
+    z = out[0].astype(np.float64)
+    pos = np.maximum(0, 1 - z)                    # y = +1
+    neg = np.maximum(0, 1 + z)                    # y = -1
+    np.testing.assert_allclose(g[0], 0.5 * -2 * pos, rtol=1e-7)
+    np.testing.assert_allclose(g[1], 0.5 * 2 * neg, rtol=1e-7)
+    assert abs(loss - 0.5 * ((pos ** 2).sum() + (neg ** 2).sum())) < 1e-12
+    assert (g[0][:2] == 0).all() and (g[1][5:] == 0).all()      # exact zeros at margin >= 1
+    assert g[0][2] != 0 and g[1][4] != 0
+
+
+def test_sqh_matches_torch_autograd(orc):
+    cfg = wl.custom(500, 64, 8, 6, positives=5)
+    out = (wl.rng(cfg, 7).standard_normal((cfg.b, cfg.m)) * 1.5).astype(np.float32)
+    off, lab = wl.gen_targets(cfg)
+    y = 2 * dense_targets(off, lab, cfg.b, cfg.m) - 1
+    scale = float(np.float32(1.0 / cfg.b))
+    loss, g = orc.sqh_loss_grad(out, off, lab, scale)
+    z = torch.tensor(out, dtype=torch.float64, requires_grad=True)
+    ref = scale * (torch.clamp(1 - torch.tensor(y) * z, min=0) ** 2).sum()
+    ref.backward()
+    assert abs(loss - ref.item()) <= 1e-12 * abs(ref.item())
+    assert_close(g, z.grad.numpy(), 1e-6, "g")
+    assert ((g == 0) == (y * out.astype(np.float64) >= 1)).all()
+
+
 # ---------------------------------------------------------------- Adam
 def test_adam_matches_torch_optimizer(orc):
     r = np.random.default_rng(5)
