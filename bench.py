@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    ap.add_argument("--sqh-sweep", action="store_true",
+                    help="also time the squared-hinge loss and the two backward calls on gradients with "
+                         "0 / 90 / 99 / 99.9 %% exact zeros (implicit negative mining, Section 3.3)")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (FETCH+WRITE, scaled)")
     args = ap.parse_args()
@@ -215,6 +218,39 @@ def main():
         "loss": loss_value, "bad_rows": n_bad, "redistributions": state["epoch"],
         "roofline": roof,
     }
+    if args.sqh_sweep:
+        # Synthetic stand-in for the gradient of a trained model under the squared hinge loss: the
+        # scores' own gradient with a seeded share of entries forced to exactly zero.
+        def timed(fn, reps=5):
+            fn()
+            a, z = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            z.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(z) / reps
+        x0 = xs[0]
+        off0, lab0 = tg[0]
+        L.forward(x0, idx, W, out, b)
+        sweep = {}
+        gbuf = torch.empty_like(out)
+        sweep["sqh_loss_ms"] = round(timed(lambda: L.sqh_loss_grad(out, off0, lab0, scale, gbuf, loss, b)), 4)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1000 * cfg.index + 77)
+        for frac in (0.0, 0.9, 0.99, 0.999):
+            L.sqh_loss_grad(out, off0, lab0, scale, gbuf, loss, b)
+            if frac > 0:
+                keep = torch.rand(gbuf.shape, generator=gen, device=dev) >= frac
+                gbuf.mul_(keep)
+                del keep
+            nz = float((gbuf != 0).float().mean().item())
+            sweep["zero_frac_%g" % frac] = {
+                "nonzero_share": round(nz, 5),
+                "backward_weight_ms": round(timed(lambda: L.backward_weight(gbuf, x0, idx, gW, b)), 4),
+                "backward_input_ms": round(timed(lambda: L.backward_input(gbuf, idx, W, gx, b)), 4)}
+        res["sqh_zero_skipping"] = sweep
+        del gbuf
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))

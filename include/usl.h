@@ -88,6 +88,17 @@ usl_status usl_bce_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_
                              const int32_t* tgt_lab, float scale, float* g, float* loss,
                              int32_t b);
 
+/* One-vs-all squared hinge loss, the paper's main loss (Section 3.3), on the same sparse targets:
+ *   s[i][j] = +1 iff j is listed for instance i, else -1
+ *   loss = scale * sum_ij max(0, 1 - s*z)^2,   g[i][j] = scale * (-2 * s * max(0, 1 - s*z))
+ * g is exactly zero wherever s*z >= 1 ("implicit negative mining"): usl_backward_weight and
+ * usl_backward_input skip the work of zero entries of g (wavefront- and workgroup-wide in the
+ * former, per 32-instance piece of a label's gradient in the latter); results are those of the
+ * unskipped sums for finite inputs.  g may be the same buffer as out. */
+usl_status usl_sqh_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_off,
+                             const int32_t* tgt_lab, float scale, float* g, float* loss,
+                             int32_t b);
+
 /* Gradient of the connection values (Section 3.3, Algorithm 3):
  * grad_W[j][t] = sum_i g[i][j] * x[i][idx[j][t]].  grad_W is overwritten. */
 usl_status usl_backward_weight(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx,

@@ -145,6 +145,45 @@ k_transpose(const float* __restrict__ in, float* __restrict__ out, int64_t R, in
     }
 }
 
+// gT[j][i] = g[i][j], and for every label j and tile of 32 instances a byte that tells whether any of
+// the 32 values is non-zero, plus the number of such (label, tile) cells in a 1/64 sample of the labels.  A squared-hinge gradient
+// is zero for every easy negative (Section 3.3), and the gather below skips those pieces.
+// blockIdx.y is the tile, so the 32 instances of a block are exactly one tile.
+__global__ void __launch_bounds__(256)
+k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, int64_t m, int64_t bp,
+              uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int64_t r0 = (int64_t)blockIdx.y * 32, c0 = (int64_t)blockIdx.x * 32;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t r = r0 + ty + 8 * q, cc = c0 + tx;
+        tile[ty + 8 * q][tx] = (r < b && cc < m) ? g[r * m + cc] : 0.f;
+    }
+    __syncthreads();
+    __shared__ uint32_t block_cells;
+    if (threadIdx.x == 0) block_cells = 0;
+    uint32_t cells = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int64_t cc = c0 + ty + 8 * q, r = r0 + tx;   // label cc, instance r
+        const float v = tile[tx][ty + 8 * q];
+        if (cc < m && r < b) gT[cc * bp + r] = v;
+        const unsigned long long bal = __ballot(v != 0.f);
+        const bool any = ((bal >> (threadIdx.x & 32)) & 0xFFFFFFFFull) != 0;   // my half-wavefront = one label
+        if (tx == 0 && cc < m) {
+            nzf[(size_t)blockIdx.y * m + cc] = any ? 1 : 0;
+            cells += any ? 1u : 0u;
+        }
+    }
+    // the count only steers a heuristic: one block of labels in 64 is sampled, one atomic per block
+    if ((blockIdx.x & 63) == 0) {
+        if (cells) atomicAdd(&block_cells, cells);
+        __syncthreads();
+        if (threadIdx.x == 0 && block_cells) atomicAdd(nz_cells, block_cells);
+    }
+}
+
 // One launch per label window: launch boundaries are what keeps all workgroups of an XCD inside the
 // same window (a single persistent sweep, with or without a soft pacing counter, drifted apart and
 // lost the L2 reuse -- measured slower).  blockIdx.x = tile of 32 instances (fastest, so that a
@@ -154,7 +193,8 @@ __global__ void __launch_bounds__(256)
 k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ ptr /* this window's d+1 offsets */,
                    const int32_t* __restrict__ label, float* __restrict__ gxT, int d, int bp,
-                   int accumulate) {
+                   int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
+                   int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
     const int c = blockIdx.y * 32 + (threadIdx.x >> 3);
     const int i0 = blockIdx.x * 32 + (threadIdx.x & 7) * 4;
     if (c >= d || i0 >= bp) return;
@@ -162,6 +202,37 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
     const uint32_t p1 = ptr[c + 1];
     const float* col = gT + i0;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // Mostly-zero gradient (decided on the device from the cell count, the same for every lane):
+    // look the piece up in the flag table first and fetch only pieces that hold something.
+    if (*nz_cells < sparse_below) {
+        const uint8_t* fl = nzf + (size_t)blockIdx.x * m;
+        for (; p + 4 <= p1; p += 4) {
+            int32_t j[4];
+            uint8_t f[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) j[q] = label[p + q];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) f[q] = fl[j[q]];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (f[q]) {
+                    const float w = wl[p + q];
+                    const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j[q] * bp);
+                    acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
+                    acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
+                }
+            }
+        }
+        for (; p < p1; ++p) {
+            const int32_t j = label[p];
+            if (fl[j]) {
+                const float w = wl[p];
+                const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j * bp);
+                acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
+                acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
+            }
+        }
+    }
     for (; p + 4 <= p1; p += 4) {
         int32_t j[4];
         float w[4];
@@ -265,17 +336,29 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
                                (const uint16_t*)W, c->csc_slot, N, c->csc_w);
     }
-    {   // gT[m][bp] = transpose of g[b][m]
-        dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));
-        hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
-                           c->m, (int64_t)bp);
+    const int ntile = (bp + 31) / 32;
+    USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
+    if (!c->counter64) {
+        size_t cap = 0;
+        USL_TRY(usl_reserve(c, (void**)&c->counter64, &cap, 64));
     }
+    uint32_t* nz_cells = reinterpret_cast<uint32_t*>(c->counter64) + 4;
+    {   // gT[m][bp] = transpose of g[b][m], with the zero flags of every (label, tile) piece
+        hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, nz_cells, (size_t)1);
+        dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)ntile);
+        hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
+                           (int64_t)bp, c->nz_flags, nz_cells);
+    }
+    // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
+    const uint64_t sampled_labels = (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32;
+    const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
+    const uint32_t sparse_below = (uint32_t)(cells / 2 > 0xFFFFFFFFull ? 0xFFFFFFFFull : cells / 2);
     {
         dim3 grid((unsigned)((bp + 31) / 32), (unsigned)((c->d + 31) / 32));
         for (int w = 0; w < nwin; ++w)
             hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
                                c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d, bp,
-                               w > 0 ? 1 : 0);
+                               w > 0 ? 1 : 0, c->nz_flags, c->m, nz_cells, sparse_below);
     }
     {   // grad_x[b][d] = transpose of gxT[d][bp] (first b columns)
         dim3 grid((unsigned)((b + 31) / 32), (unsigned)((c->d + 31) / 32));

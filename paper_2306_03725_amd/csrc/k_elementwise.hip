@@ -1,4 +1,5 @@
-// Sparse-target binary cross-entropy (loss + gradient in one pass over the scores) and Adam.
+// Sparse-target one-vs-all losses (binary cross-entropy, squared hinge: loss + gradient in one pass
+// over the scores) and Adam.
 // Both are pure HBM streams: one read and one write of every element, 16 bytes per lane.
 #include "usl_internal.h"
 
@@ -10,20 +11,31 @@ constexpr int BCE_CHUNK = BCE_NT * BCE_PER_THREAD;
 constexpr int BCE_MAX_HITS = 512;
 
 struct Bce1 { float g, l; };
-// l(z, y) = max(z,0) - z*y + log(1 + exp(-|z|));  dl/dz = sigmoid(z) - y
+enum { LOSS_BCE = 0, LOSS_SQH = 1 };
+// y is 0 or 1.
+// BCE:           l = max(z,0) - z*y + log(1 + exp(-|z|));  dl/dz = sigmoid(z) - y
+// squared hinge: s = 2y-1, l = max(0, 1 - s*z)^2;          dl/dz = -2*s*max(0, 1 - s*z)  (exact zeros)
+template <int LOSS>
 __device__ __forceinline__ Bce1 bce_one(float z, float y, float scale) {
-    const float e = __expf(-fabsf(z));
-    const float r = __frcp_rn(1.f + e);
-    const float sig = z >= 0.f ? r : e * r;
     Bce1 o;
-    o.g = scale * (sig - y);
-    o.l = fmaxf(z, 0.f) - z * y + __logf(1.f + e);
+    if (LOSS == LOSS_BCE) {
+        const float e = __expf(-fabsf(z));
+        const float r = __frcp_rn(1.f + e);
+        const float sig = z >= 0.f ? r : e * r;
+        o.g = scale * (sig - y);
+        o.l = fmaxf(z, 0.f) - z * y + __logf(1.f + e);
+    } else {
+        const float sgn = 2.f * y - 1.f;
+        const float margin = fmaxf(0.f, fmaf(-sgn, z, 1.f));
+        o.g = scale * (-2.f * sgn * margin);
+        o.l = margin * margin;
+    }
     return o;
 }
 
 // grid (label chunks, b).  The positives of the instance that fall into the block's label range
 // are collected in LDS first; nearly always there are none, so the per-element test is free.
-template <bool VEC>
+template <bool VEC, int LOSS>
 __global__ void __launch_bounds__(BCE_NT)
 k_bce(const float* out, const int64_t* __restrict__ tgt_off, const int32_t* __restrict__ tgt_lab,
       float scale, float* g, double* __restrict__ partials, int64_t m) {
@@ -68,13 +80,13 @@ k_bce(const float* out, const int64_t* __restrict__ tgt_off, const int32_t* __re
         }
         if (VEC && j + 4 <= j1) {
             const float4 z = *reinterpret_cast<const float4*>(zrow + j);
-            const Bce1 a = bce_one(z.x, y[0], scale), b2 = bce_one(z.y, y[1], scale),
-                       c = bce_one(z.z, y[2], scale), dd = bce_one(z.w, y[3], scale);
+            const Bce1 a = bce_one<LOSS>(z.x, y[0], scale), b2 = bce_one<LOSS>(z.y, y[1], scale),
+                       c = bce_one<LOSS>(z.z, y[2], scale), dd = bce_one<LOSS>(z.w, y[3], scale);
             *reinterpret_cast<float4*>(grow + j) = make_float4(a.g, b2.g, c.g, dd.g);
             lsum += (a.l + b2.l) + (c.l + dd.l);
         } else {
             for (int q = 0; q < 4 && j + q < j1; ++q) {
-                const Bce1 a = bce_one(zrow[j + q], y[q], scale);
+                const Bce1 a = bce_one<LOSS>(zrow[j + q], y[q], scale);
                 grow[j + q] = a.g;
                 lsum += a.l;
             }
@@ -171,8 +183,8 @@ k_adam(TS* __restrict__ W, const float* __restrict__ gW, float* __restrict__ m1,
 
 }  // namespace
 
-usl_status usl_launch_bce(usl_ctx* c, const float* out, const int64_t* tgt_off,
-                          const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b) {
+usl_status usl_launch_loss(usl_ctx* c, int loss_kind, const float* out, const int64_t* tgt_off,
+                           const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b) {
     const int64_t nchunk = (c->m + BCE_CHUNK - 1) / BCE_CHUNK;
     const size_t nblk = (size_t)nchunk * b;
     size_t cap = c->bce_partials_cap;
@@ -180,15 +192,15 @@ usl_status usl_launch_bce(usl_ctx* c, const float* out, const int64_t* tgt_off,
     c->bce_partials_cap = cap;
     const bool vec = (c->m % 4 == 0) && ((uintptr_t)out % 16 == 0) && ((uintptr_t)g % 16 == 0);
     dim3 grid((unsigned)nchunk, (unsigned)b);
-    if (vec)
-        hipLaunchKernelGGL(k_bce<true>, grid, dim3(BCE_NT), 0, c->stream, out, tgt_off, tgt_lab, scale,
-                           g, c->bce_partials, c->m);
-    else
-        hipLaunchKernelGGL(k_bce<false>, grid, dim3(BCE_NT), 0, c->stream, out, tgt_off, tgt_lab, scale,
-                           g, c->bce_partials, c->m);
-    USL_TRY(usl_check_launch(c, "bce"));
+#define USL_LOSS(VEC, KIND)                                                                          \
+    hipLaunchKernelGGL((k_bce<VEC, KIND>), grid, dim3(BCE_NT), 0, c->stream, out, tgt_off, tgt_lab,  \
+                       scale, g, c->bce_partials, c->m)
+    if (loss_kind == LOSS_BCE) { if (vec) USL_LOSS(true, LOSS_BCE); else USL_LOSS(false, LOSS_BCE); }
+    else                       { if (vec) USL_LOSS(true, LOSS_SQH); else USL_LOSS(false, LOSS_SQH); }
+#undef USL_LOSS
+    USL_TRY(usl_check_launch(c, "loss"));
     hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, c->bce_partials, nblk, scale, loss);
-    return usl_check_launch(c, "bce_finish");
+    return usl_check_launch(c, "loss_finish");
 }
 
 usl_status usl_launch_adam(usl_ctx* c, void* W, const float* grad_W, float* m1, float* m2, float lr,

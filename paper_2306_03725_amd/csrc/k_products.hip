@@ -37,6 +37,7 @@ struct TileGeom {
     int nparts;         // slices per row
     int inst_per_group; // instances handled by one blockIdx.y
     int vec_ok;         // 16-byte copies allowed
+    int flag_offset;    // byte offset in LDS of the per-wavefront flags of backward_weight
 };
 
 // ---------------------------------------------------------------------------- forward
@@ -218,6 +219,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 for (int l = 0; l < LPT; ++l) {
                     const int64_t j = jme + (int64_t)l * NT;
                     const float gv = j < m ? g[(size_t)(it + r) * m + j] : 0.f;
+                    if (!__any(gv != 0.f)) continue;
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t)
@@ -226,25 +228,51 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             }
         }
     } else {
+        // Zero entries of g contribute nothing (Algorithm 3 skips them): a label whose gradient is
+        // zero in all 64 lanes of the wavefront skips its gathers, and an instance whose gradient is
+        // zero for every label of the workgroup is not even staged.  The gradient of the next
+        // instance is fetched one instance ahead so that this test costs no memory round trip.
+        uint32_t* live_flags = reinterpret_cast<uint32_t*>(lds_raw + tg.flag_offset);
+        float gnext[LPT];
+#pragma unroll
+        for (int l = 0; l < LPT; ++l) {
+            const int64_t j = jme + (int64_t)l * NT;
+            gnext[l] = (j < m && i_begin < i_end) ? g[(size_t)i_begin * m + j] : 0.f;
+        }
 #pragma unroll 1
         for (int i = i_begin; i < i_end; ++i) {
             float gv[LPT];
+            bool any = false;
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) { gv[l] = gnext[l]; any = any || gv[l] != 0.f; }
+            // workgroup-wide OR through one word per wavefront behind the row buffer (two sets,
+            // alternating, so the next instance's writers cannot overtake this instance's readers);
+            // the barrier is the one that frees the row buffer anyway
+            uint32_t* wf = live_flags + (i & 1) * (NT / 64);
+            const bool wave_any = __any(any);
+            if ((threadIdx.x & 63) == 0) wf[threadIdx.x >> 6] = wave_any ? 1u : 0u;
+            __syncthreads();
+            uint32_t live = 0;
+#pragma unroll
+            for (int q = 0; q < NT / 64; ++q) live |= wf[q];
 #pragma unroll
             for (int l = 0; l < LPT; ++l) {
                 const int64_t j = jme + (int64_t)l * NT;
-                gv[l] = j < m ? g[(size_t)i * m + j] : 0.f;
+                gnext[l] = (j < m && i + 1 < i_end) ? g[(size_t)(i + 1) * m + j] : 0.f;
             }
+            if (!live) continue;
             const int nparts = MODE == 1 ? tg.nparts : 1;
 #pragma unroll 1
             for (int part = 0; part < nparts; ++part) {
                 const int c0 = part * tg.part_cols;
                 const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
-                __syncthreads();
+                if (part > 0) __syncthreads();
                 stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
                 if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
+                    if (!__any(gv[l] != 0.f)) continue;
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
@@ -342,6 +370,9 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     *groups = G;
     *lds_bytes = tg.nparts == 1 ? (size_t)tg.rows_per_tile * row_bytes
                                 : (size_t)tg.part_cols * esize + 128;   // + the zero words
+    *lds_bytes = (*lds_bytes + 15) & ~(size_t)15;
+    tg.flag_offset = (int)*lds_bytes;
+    *lds_bytes += 256;                                                   // + per-wavefront flags
     return tg;
 }
 

@@ -29,7 +29,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (!c) return USL_OK;
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
-                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->csc_w, c->gT, c->gxT,
+                        c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->csc_w, c->gT, c->gxT, c->nz_flags,
                         c->slot_order};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
@@ -131,7 +131,18 @@ extern "C" usl_status usl_bce_loss_grad(usl_ctx* c, const float* out, const int6
     if (!(scale == scale) || isinf(scale)) USL_FAIL(c, USL_EINVAL, "scale is not finite");
     USL_TRY(check_batch(c, b));
     USL_TRY(usl_prepare_device(c));
-    return usl_launch_bce(c, out, tgt_off, tgt_lab, scale, g, loss, b);
+    return usl_launch_loss(c, 0, out, tgt_off, tgt_lab, scale, g, loss, b);
+}
+
+extern "C" usl_status usl_sqh_loss_grad(usl_ctx* c, const float* out, const int64_t* tgt_off,
+                                        const int32_t* tgt_lab, float scale, float* g, float* loss,
+                                        int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(out); NEED(tgt_off); NEED(tgt_lab); NEED(g); NEED(loss);
+    if (!(scale == scale) || isinf(scale)) USL_FAIL(c, USL_EINVAL, "scale is not finite");
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_loss(c, 1, out, tgt_off, tgt_lab, scale, g, loss, b);
 }
 
 extern "C" usl_status usl_backward_weight(usl_ctx* c, const float* g, const void* x,

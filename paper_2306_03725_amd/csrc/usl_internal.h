@@ -38,6 +38,7 @@ struct usl_ctx {
     uint8_t* slot_order;           // [m*k] slot read at step s
     const int32_t* slot_order_for; // idx pointer it was computed from (NULL = stale)
     float* gT;                size_t gT_cap;   // [m][bp] transposed upstream gradient
+    uint8_t* nz_flags;        size_t nz_flags_cap;   // [tiles][m] 1 = that 32-instance piece of gT is not all zero
     float* gxT;               size_t gxT_cap;  // [d][bp] transposed input gradient
 };
 
@@ -75,8 +76,9 @@ usl_status usl_launch_backward_weight(usl_ctx* ctx, const float* g, const void* 
                                       const int32_t* idx, float* grad_W, int32_t b);
 usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx,
                                      const void* W, float* grad_x, int32_t b);
-usl_status usl_launch_bce(usl_ctx* ctx, const float* out, const int64_t* tgt_off,
-                          const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
+// loss_kind: 0 = binary cross-entropy, 1 = squared hinge
+usl_status usl_launch_loss(usl_ctx* ctx, int loss_kind, const float* out, const int64_t* tgt_off,
+                           const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
 usl_status usl_launch_adam(usl_ctx* ctx, void* W, const float* grad_W, float* m1, float* m2,
                            float lr, float beta1, float beta2, float eps, float inv_c1,
                            float inv_c2);

@@ -16,7 +16,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 
 # every symbol include/usl.h declares
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
-           "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad",
+           "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
 
@@ -36,6 +36,7 @@ _sig = {
     "usl_init_indices": [_vp, _vp, _u64],
     "usl_forward": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
+    "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_backward_weight": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_backward_input": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32],
@@ -111,6 +112,10 @@ class Layer:
 
     def bce_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
         self._ck(_lib.usl_bce_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
+                                        _ptr(g), _ptr(loss), b))
+
+    def sqh_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
+        self._ck(_lib.usl_sqh_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
                                         _ptr(g), _ptr(loss), b))
 
     def backward_weight(self, g, x, idx, grad_W, b):

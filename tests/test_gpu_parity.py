@@ -134,6 +134,60 @@ def test_bce(usl, gu, orc, name):
     assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
 
 
+@pytest.mark.parametrize("name", ["tiny", "ragged_small", "odd_d", "big_blocks", "one"])
+def test_squared_hinge(usl, gu, orc, name):
+    cfg = make(name)
+    m, b = cfg.m, cfg.b
+    r = wl.rng(cfg, 7)
+    out = (r.standard_normal((b, m)) * 1.5).astype(np.float32)
+    flat = out.reshape(-1)
+    flat[:: max(1, flat.size // 40)] = r.choice([1.0, -1.0, 0.0, 5.0, -5.0], size=len(flat[:: max(1, flat.size // 40)]))
+    off, lab = wl.gen_targets(cfg)
+    scale = float(np.float32(1.0 / b))
+    L = usl.Layer(m, cfg.d, cfg.k, b)
+    d_out = gu.dev(out)
+    g, loss = gu.empty((b, m)), gu.empty((1,))
+    L.sqh_loss_grad(d_out, gu.dev(off), gu.dev(lab), scale, g, loss, b)
+    ref_loss, ref_g = orc.sqh_loss_grad(out, off, lab, scale)
+    got = gu.host(g)
+    assert_close(got, ref_g, 1e-5, "g")
+    np.testing.assert_array_equal(got == 0, ref_g == 0)          # the exact zeros are the same ones
+    assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
+    L.sqh_loss_grad(d_out, gu.dev(off), gu.dev(lab), scale, d_out, loss, b)      # in place
+    np.testing.assert_array_equal(gu.host(d_out), got)
+
+
+SPARSE_G = [("tiny", "f32", 0.9), ("ragged_small", "f32", 0.99), ("k64", "f32", 0.97), ("big_blocks", "f32", 0.999),
+            ("big_one_group", "f32", 0.9), ("sliced_small", "bf16", 0.95), ("k5", "f32", 0.9), ("big_blocks", "bf16", 1.0)]
+
+
+@pytest.mark.parametrize("name,storage,zero_frac", SPARSE_G)
+def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_frac):
+    """Zero entries of g are skipped by the backward kernels; the sums must be those of the oracle,
+    which skips nothing.  Patterns: iid zeros, whole instances zero, whole label ranges zero."""
+    cfg = make(name, storage)
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    idx, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
+    r = wl.rng(cfg, 21)
+    g[r.random(g.shape) < zero_frac] = 0.0
+    g[b // 2] = 0.0                                  # an instance that contributes nothing
+    g[:, : m // 3] = 0.0                             # a range of labels that contributes nothing
+    if b > 2:
+        g[b - 1, m - 1] = 0.25                       # ... and a lone survivor at the very end
+    L = usl.Layer(m, d, k, b, storage)
+    d_idx, d_W, d_x, d_g = gu.dev(idx), gu.dev(W), gu.dev(x), gu.dev(g)
+    gW = gu.empty((m, k)).fill_(float("nan"))
+    gx = gu.empty((b, d)).fill_(float("nan"))
+    L.backward_weight(d_g, d_x, d_idx, gW, b)
+    L.backward_input(d_g, d_idx, d_W, gx, b)
+    assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W")
+    assert_close(gu.host(gx), orc.backward_input(g, idx, W, d), 1e-4, "grad_x")
+    # dense again on the same context: the sparse path must not stick
+    g2 = wl.gen_g(cfg, 1)
+    L.backward_input(gu.dev(g2), d_idx, d_W, gx, b)
+    assert_close(gu.host(gx), orc.backward_input(g2, idx, W, d), 1e-4, "grad_x dense after sparse")
+
+
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
 @pytest.mark.parametrize("n_shape", [(1024, 8), (777, 5), (3, 1), (30938, 32)])
 def test_adam(usl, gu, orc, n_shape, storage):
