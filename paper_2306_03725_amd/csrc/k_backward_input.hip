@@ -31,15 +31,43 @@ __global__ void k_zero_u32(uint32_t* p, size_t n) {
     for (; i < n; i += s) p[i] = 0;
 }
 
-// bin of slot e: (window of its label) * d + its feature
-__global__ void __launch_bounds__(256)
-k_csc_count(const int32_t* __restrict__ idx, size_t N, int k, int d, int win_labels,
-            uint32_t* __restrict__ count) {
-    const size_t s = (size_t)gridDim.x * 256;
-    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < N; e += s) {
-        const size_t j = e / (size_t)k;
-        atomicAdd(&count[(j / win_labels) * (size_t)d + idx[e]], 1u);
+// Lists are grouped by (label window, feature).  A workgroup takes one of `splits` equal shares of
+// a window's slots (contiguous in idx) and a chunk of up to 32768 features, and counts its share in
+// an LDS histogram; global memory sees one coalesced atomic per (workgroup, feature), not one per slot.
+constexpr int CSC_NT = 1024, CSC_CHUNK = 32768;
+
+__device__ __forceinline__ void csc_share(int64_t m, int k, int win_labels, int splits, size_t* e0, size_t* e1) {
+    const int w = blockIdx.x / splits, s = blockIdx.x % splits;
+    const size_t w0 = (size_t)w * win_labels * k;
+    const size_t w1 = (size_t)min((int64_t)(w + 1) * win_labels, m) * k;
+    const size_t per = (w1 - w0 + splits - 1) / splits;
+    *e0 = min(w0 + per * s, w1);
+    *e1 = min(*e0 + per, w1);
+}
+
+__device__ __forceinline__ void csc_histogram(const int32_t* __restrict__ idx, size_t e0, size_t e1, int c0, int nc,
+                                              uint32_t* hist) {
+    for (int q = threadIdx.x; q < nc; q += CSC_NT) hist[q] = 0;
+    __syncthreads();
+    for (size_t e = e0 + threadIdx.x; e < e1; e += CSC_NT) {
+        const uint32_t c = (uint32_t)(idx[e] - c0);
+        if (c < (uint32_t)nc) atomicAdd(&hist[c], 1u);
     }
+    __syncthreads();
+}
+
+// count (zeroed by the caller) += this workgroup's histogram
+__global__ void __launch_bounds__(CSC_NT)
+k_csc_count(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_labels, int splits,
+            uint32_t* __restrict__ count) {
+    extern __shared__ uint32_t hist[];
+    const int c0 = blockIdx.y * CSC_CHUNK, nc = min(CSC_CHUNK, d - c0);
+    size_t e0, e1;
+    csc_share(m, k, win_labels, splits, &e0, &e1);
+    csc_histogram(idx, e0, e1, c0, nc, hist);
+    uint32_t* dst = count + (size_t)(blockIdx.x / splits) * d + c0;
+    for (int q = threadIdx.x; q < nc; q += CSC_NT)
+        if (hist[q]) atomicAdd(&dst[q], hist[q]);
 }
 
 // Exclusive scan of count[n] into ptr[n+1] (and cursor[c] = ptr[c]) in three launches: per-chunk
@@ -103,15 +131,31 @@ k_scan_apply(uint32_t* __restrict__ cursor /* in: counts */, const uint32_t* __r
     }
 }
 
-__global__ void __launch_bounds__(256)
-k_csc_fill(const int32_t* __restrict__ idx, size_t N, int k, int d, int win_labels,
-           uint32_t* __restrict__ cursor, uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
-    const size_t s = (size_t)gridDim.x * 256;
-    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < N; e += s) {
-        const size_t j = e / (size_t)k;
-        const uint32_t pos = atomicAdd(&cursor[(j / win_labels) * (size_t)d + idx[e]], 1u);
-        slot[pos] = (uint32_t)e;
-        label[pos] = (int32_t)j;
+// Same decomposition.  The workgroup counts its share again, reserves that many places in every
+// list with one atomic on `taken` (zeroed by the caller), and hands the places out from LDS cursors.
+// The order of a list's entries is therefore not fixed; the sums that walk it do not fix theirs either.
+__global__ void __launch_bounds__(CSC_NT)
+k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_labels, int splits,
+           const uint32_t* __restrict__ ptr, uint32_t* __restrict__ taken,
+           uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
+    extern __shared__ uint32_t cur[];
+    const int c0 = blockIdx.y * CSC_CHUNK, nc = min(CSC_CHUNK, d - c0);
+    size_t e0, e1;
+    csc_share(m, k, win_labels, splits, &e0, &e1);
+    csc_histogram(idx, e0, e1, c0, nc, cur);
+    const size_t bin0 = (size_t)(blockIdx.x / splits) * d + c0;
+    for (int q = threadIdx.x; q < nc; q += CSC_NT) {
+        const uint32_t n = cur[q];
+        if (n) cur[q] = ptr[bin0 + q] + atomicAdd(&taken[bin0 + q], n);
+    }
+    __syncthreads();
+    for (size_t e = e0 + threadIdx.x; e < e1; e += CSC_NT) {
+        const uint32_t c = (uint32_t)(idx[e] - c0);
+        if (c < (uint32_t)nc) {
+            const uint32_t pos = atomicAdd(&cur[c], 1u);
+            slot[pos] = (uint32_t)e;
+            label[pos] = (int32_t)(e / (size_t)k);
+        }
     }
 }
 
@@ -291,11 +335,18 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
         }
         c->csc_win_labels = wl;
     }
-    size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
-    if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
+    const unsigned cchunks = (unsigned)((c->d + CSC_CHUNK - 1) / CSC_CHUNK);
+    int splits = (int)((2 * (size_t)c->num_cu + nwin * cchunks - 1) / (nwin * cchunks));
+    splits = splits < 1 ? 1 : splits > 16 ? 16 : splits;
+    const dim3 cgrid((unsigned)(nwin * splits), cchunks);
+    const size_t clds = (size_t)(c->d < CSC_CHUNK ? c->d : CSC_CHUNK) * 4;
+    USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(k_csc_count),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)clds));
+    USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(k_csc_fill),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)clds));
     hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
-    hipLaunchKernelGGL(k_csc_count, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx, N, c->k,
-                       c->d, wl, c->csc_cursor);
+    hipLaunchKernelGGL(k_csc_count, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
+                       splits, c->csc_cursor);
     const size_t nchunks = (nbins + SCAN_CHUNK - 1) / SCAN_CHUNK;
     {
         size_t cap = c->tie_counts_cap;  // the redistribution's block-count buffer doubles as scan scratch
@@ -308,8 +359,9 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
                        c->csc_ptr + nbins);
     hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, c->csc_cursor,
                        c->tie_counts, nbins, c->csc_ptr);
-    hipLaunchKernelGGL(k_csc_fill, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx, N, c->k,
-                       c->d, wl, c->csc_cursor, c->csc_slot, c->csc_label);
+    hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
+    hipLaunchKernelGGL(k_csc_fill, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
+                       splits, c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label);
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
     return USL_OK;
