@@ -123,6 +123,27 @@ def sqh_loss_grad(out, tgt_off, tgt_lab, scale):
     return loss.value, g
 
 
+def topk(out, kk):
+    """The kk best labels of every row, best first (ties: smaller label); returns (labels, scores)."""
+    _chk(out, np.float32)
+    b, m = out.shape
+    assert 1 <= kk <= m
+    lab = np.empty((b, kk), np.int32)
+    val = np.empty((b, kk), np.float32)
+    lib().orc_topk(_p(out), ctypes.c_int64(m), ctypes.c_int32(b), ctypes.c_int32(kk), _p(lab), _p(val))
+    return lab, val
+
+
+def precision_hits(top_lab, tgt_off, tgt_lab):
+    """hits[r] = number of instances whose rank-r prediction is a target; P@k = hits[:k].sum()/(k*b)."""
+    _chk(top_lab, np.int32), _chk(tgt_off, np.int64), _chk(tgt_lab, np.int32)
+    b, kk = top_lab.shape
+    hits = np.zeros(kk, np.int64)
+    lib().orc_precision_hits(_p(top_lab), _p(tgt_off), _p(tgt_lab), ctypes.c_int32(b), ctypes.c_int32(kk),
+                             _p(hits))
+    return hits
+
+
 def adam_step(W, grad_W, m1, m2, t, lr, beta1, beta2, eps):
     """In-place Adam on W, m1, m2.  For bfloat16 W returns the unrounded float32 values."""
     _chk(W), _chk(grad_W, np.float32), _chk(m1, np.float32), _chk(m2, np.float32)

@@ -145,6 +145,45 @@ void orc_sqh_loss_grad(const float* out, const int64_t* tgt_off, const int32_t* 
     *loss_out = (double)scale * total;
 }
 
+/* Prediction (Section 2): the kk highest-scoring labels of every instance, best first.
+ * Label p ranks before label q if out[p] > out[q], or if the scores compare equal and p < q
+ * (so -0 and +0 tie).  Written as the definition: kk times, walk the whole row and take the best
+ * label not taken yet.  Scores must not be NaN.  top_lab, top_val: [b][kk]. */
+void orc_topk(const float* out, int64_t m, int32_t b, int32_t kk, int32_t* top_lab, float* top_val) {
+#pragma omp parallel for schedule(static)
+    for (int32_t i = 0; i < b; ++i) {
+        const float* z = out + (int64_t)i * m;
+        uint8_t* taken = (uint8_t*)calloc((size_t)m, 1);
+        for (int32_t r = 0; r < kk; ++r) {
+            int64_t best = -1;
+            for (int64_t j = 0; j < m; ++j) {
+                if (taken[j]) continue;
+                if (best < 0 || z[j] > z[best]) best = j; /* strict: the first of equals stays */
+            }
+            taken[best] = 1;
+            top_lab[(int64_t)i * kk + r] = (int32_t)best;
+            top_val[(int64_t)i * kk + r] = z[best];
+        }
+        free(taken);
+    }
+}
+
+/* Precision at k (Section 2, the equation that defines P@k): with y the 0/1 target vector and
+ * yhat the 0/1 vector of the k predicted labels, P@k = (1/k) * sum_j y[j]*yhat[j], averaged over
+ * instances.  hits[r] counts the instances whose rank-r prediction (0-based) is one of their
+ * targets, so that P@k = (hits[0] + ... + hits[k-1]) / (k * b) for every k <= kk at once. */
+void orc_precision_hits(const int32_t* top_lab, const int64_t* tgt_off, const int32_t* tgt_lab,
+                        int32_t b, int32_t kk, int64_t* hits) {
+    for (int32_t r = 0; r < kk; ++r) hits[r] = 0;
+    for (int32_t i = 0; i < b; ++i)
+        for (int32_t r = 0; r < kk; ++r) {
+            int hit = 0;
+            for (int64_t p = tgt_off[i]; p < tgt_off[i + 1]; ++p)
+                if (tgt_lab[p] == top_lab[(int64_t)i * kk + r]) hit = 1;
+            hits[r] += hit;
+        }
+}
+
 /* Adam (Kingma & Ba, Algorithm 1; the optimizer named in Section 4.1) on the m*k values.
  * t is the 1-based step count.  With storage==1, W is bfloat16: the updated value is
  * rounded float -> bfloat16 (nearest even) and, if W_f32_out is not NULL, the unrounded

@@ -169,32 +169,33 @@ k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, size_t N
         wl[p] = usl_load_f32<TS>(W, (size_t)slot[p]);
 }
 
-// out[c][r] = in[r][c] for r < R, c < C; rows of in / out are ld_in / ld_out elements apart.
+// grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.x = tile, blockIdx.y = block of 32 features.
 __global__ void __launch_bounds__(256)
-k_transpose(const float* __restrict__ in, float* __restrict__ out, int64_t R, int64_t C,
-            int64_t ld_in, int64_t ld_out) {
+k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, int64_t d) {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int64_t r0 = (int64_t)blockIdx.y * 32, c0 = (int64_t)blockIdx.x * 32;
+    const int64_t i0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int64_t r = r0 + ty + 8 * q, cc = c0 + tx;
-        if (r < R && cc < C) tile[ty + 8 * q][tx] = in[r * ld_in + cc];
+        const int64_t c = c0 + ty + 8 * q;
+        if (c < d) tile[ty + 8 * q][tx] = gxT[((size_t)blockIdx.x * d + c) * 32 + tx];
     }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int64_t cc = c0 + ty + 8 * q, r = r0 + tx;
-        if (cc < C && r < R) out[cc * ld_out + r] = tile[tx][ty + 8 * q];
+        const int64_t i = i0 + ty + 8 * q, c = c0 + tx;
+        if (i < b && c < d) grad_x[i * d + c] = tile[tx][ty + 8 * q];
     }
 }
 
-// gT[j][i] = g[i][j], and for every label j and tile of 32 instances a byte that tells whether any of
+// gT[i/32][j][i%32] = g[i][j] (one contiguous 128-byte piece per label and tile of 32 instances: with rows of
+// b values a tile's pieces would sit a fixed distance apart and crowd into a fraction of the L2's sets and
+// channels), and for every label j and tile of 32 instances a byte that tells whether any of
 // the 32 values is non-zero, plus the number of such (label, tile) cells in a 1/64 sample of the labels.  A squared-hinge gradient
 // is zero for every easy negative (Section 3.3), and the gather below skips those pieces.
 // blockIdx.y is the tile, so the 32 instances of a block are exactly one tile.
 __global__ void __launch_bounds__(256)
-k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, int64_t m, int64_t bp,
+k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, int64_t m,
               uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells) {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
@@ -212,7 +213,7 @@ k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, in
     for (int q = 0; q < 4; ++q) {
         const int64_t cc = c0 + ty + 8 * q, r = r0 + tx;   // label cc, instance r
         const float v = tile[tx][ty + 8 * q];
-        if (cc < m && r < b) gT[cc * bp + r] = v;
+        if (cc < m) gT[((size_t)blockIdx.y * m + cc) * 32 + tx] = v;   // instances past b hold zeros
         const unsigned long long bal = __ballot(v != 0.f);
         const bool any = ((bal >> (threadIdx.x & 32)) & 0xFFFFFFFFull) != 0;   // my half-wavefront = one label
         if (tx == 0 && cc < m) {
@@ -236,15 +237,14 @@ k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, in
 __global__ void __launch_bounds__(256)
 k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ ptr /* this window's d+1 offsets */,
-                   const int32_t* __restrict__ label, float* __restrict__ gxT, int d, int bp,
+                   const int32_t* __restrict__ label, float* __restrict__ gxT, int d,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
                    int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
     const int c = blockIdx.y * 32 + (threadIdx.x >> 3);
-    const int i0 = blockIdx.x * 32 + (threadIdx.x & 7) * 4;
-    if (c >= d || i0 >= bp) return;
+    if (c >= d) return;
     uint32_t p = ptr[c];
     const uint32_t p1 = ptr[c + 1];
-    const float* col = gT + i0;
+    const float* col = gT + (size_t)blockIdx.x * m * 32 + (threadIdx.x & 7) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     // Mostly-zero gradient (decided on the device from the cell count, the same for every lane):
     // look the piece up in the flag table first and fetch only pieces that hold something.
@@ -261,7 +261,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             for (int q = 0; q < 4; ++q) {
                 if (f[q]) {
                     const float w = wl[p + q];
-                    const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j[q] * bp);
+                    const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
                     acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
                     acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
                 }
@@ -271,36 +271,56 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             const int32_t j = label[p];
             if (fl[j]) {
                 const float w = wl[p];
-                const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j * bp);
+                const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j * 32);
                 acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
                 acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
             }
         }
     }
-    for (; p + 4 <= p1; p += 4) {
-        int32_t j[4];
-        float w[4];
-        float4 v[4];
+    // Lists are short (m*k/d per feature and 16384 labels: 16 at Large), so the walk is a chain of
+    // dependent load latencies, not a stream.  U entries go per trip, the tail is masked rather than
+    // walked one by one, and the next trip's (label, weight) pairs are requested while this trip's
+    // pieces are in flight.  The 8 lanes of a group read the same entry.
+    constexpr int U = 8;
+    if (p < p1) {
+        int32_t j[U];
+        float w[U];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {   // the 8 lanes of a group read the same entry; the next ones hit L1
-            j[q] = label[p + q];
-            w[q] = wl[p + q];
+        for (int q = 0; q < U; ++q) {
+            const uint32_t pp = min(p + q, p1 - 1);
+            j[q] = label[pp];
+            w[q] = wl[pp];
         }
+        while (true) {
+            float4 v[U];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * bp);
+            for (int q = 0; q < U; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
+            const uint32_t pn = p + U;
+            int32_t jn[U];
+            float wn[U];
+            if (pn < p1) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            acc.x = fmaf(w[q], v[q].x, acc.x); acc.y = fmaf(w[q], v[q].y, acc.y);
-            acc.z = fmaf(w[q], v[q].z, acc.z); acc.w = fmaf(w[q], v[q].w, acc.w);
+                for (int q = 0; q < U; ++q) {
+                    const uint32_t pp = min(pn + q, p1 - 1);
+                    jn[q] = label[pp];
+                    wn[q] = wl[pp];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const bool live = p + q < p1;   // a masked entry adds 0*0, whatever the repeated piece holds
+                const float ww = live ? w[q] : 0.f;
+                const float4 vv = live ? v[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                acc.x = fmaf(ww, vv.x, acc.x); acc.y = fmaf(ww, vv.y, acc.y);
+                acc.z = fmaf(ww, vv.z, acc.z); acc.w = fmaf(ww, vv.w, acc.w);
+            }
+            if (pn >= p1) break;
+            p = pn;
+#pragma unroll
+            for (int q = 0; q < U; ++q) { j[q] = jn[q]; w[q] = wn[q]; }
         }
     }
-    for (; p < p1; ++p) {
-        const float w = wl[p];
-        const float4 v = *reinterpret_cast<const float4*>(col + (size_t)label[p] * bp);
-        acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
-        acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
-    }
-    float4* dst = reinterpret_cast<float4*>(gxT + (size_t)c * bp + i0);
+    float4* dst = reinterpret_cast<float4*>(gxT + ((size_t)blockIdx.x * d + c) * 32 + (threadIdx.x & 7) * 4);
     if (accumulate) {
         const float4 o = *dst;
         acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
@@ -373,11 +393,11 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
                                      float* grad_x, int32_t b) {
     if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) USL_TRY(build_csc(c, idx));
     const size_t N = (size_t)c->m * c->k;
-    const int bp = (b + 3) & ~3;
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
-    USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)c->m * bp * 4));
-    USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)c->d * bp * 4));
+    const int ntile = (b + 31) / 32;
+    USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)ntile * c->m * 32 * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)ntile * c->d * 32 * 4));
     {   // weights in list order
         size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
         if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
@@ -388,34 +408,32 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
                                (const uint16_t*)W, c->csc_slot, N, c->csc_w);
     }
-    const int ntile = (bp + 31) / 32;
     USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
     if (!c->counter64) {
         size_t cap = 0;
         USL_TRY(usl_reserve(c, (void**)&c->counter64, &cap, 64));
     }
     uint32_t* nz_cells = reinterpret_cast<uint32_t*>(c->counter64) + 4;
-    {   // gT[m][bp] = transpose of g[b][m], with the zero flags of every (label, tile) piece
+    {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
         hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, nz_cells, (size_t)1);
         dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)ntile);
         hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
-                           (int64_t)bp, c->nz_flags, nz_cells);
+                           c->nz_flags, nz_cells);
     }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t sampled_labels = (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32;
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
     const uint32_t sparse_below = (uint32_t)(cells / 2 > 0xFFFFFFFFull ? 0xFFFFFFFFull : cells / 2);
     {
-        dim3 grid((unsigned)((bp + 31) / 32), (unsigned)((c->d + 31) / 32));
+        dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
         for (int w = 0; w < nwin; ++w)
             hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                               c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d, bp,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d,
                                w > 0 ? 1 : 0, c->nz_flags, c->m, nz_cells, sparse_below);
     }
-    {   // grad_x[b][d] = transpose of gxT[d][bp] (first b columns)
-        dim3 grid((unsigned)((b + 31) / 32), (unsigned)((c->d + 31) / 32));
-        hipLaunchKernelGGL(k_transpose, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)c->d,
-                           (int64_t)b, (int64_t)bp, (int64_t)c->d);
+    {
+        dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
+        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d);
     }
     return usl_check_launch(c, "backward_input");
 }

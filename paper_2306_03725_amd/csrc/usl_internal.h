@@ -37,9 +37,9 @@ struct usl_ctx {
     // bank-aware order in which a label's slots are visited by the LDS gathers (performance only)
     uint8_t* slot_order;           // [m*k] slot read at step s
     const int32_t* slot_order_for; // idx pointer it was computed from (NULL = stale)
-    float* gT;                size_t gT_cap;   // [m][bp] transposed upstream gradient
+    float* gT;                size_t gT_cap;   // [tiles][m][32] upstream gradient, one 128-byte piece per (tile of 32 instances, label)
     uint8_t* nz_flags;        size_t nz_flags_cap;   // [tiles][m] 1 = that 32-instance piece of gT is not all zero
-    float* gxT;               size_t gxT_cap;  // [d][bp] transposed input gradient
+    float* gxT;               size_t gxT_cap;  // [tiles][d][32] input gradient in the same layout
 };
 
 #define USL_FAIL(ctx, code, ...)                                   \

@@ -1,5 +1,7 @@
 """Pins of the CPU oracle to things other than itself: the paper's worked example, dense
 brute force through numpy/torch library routines, closed forms and invariants.  No GPU."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -367,3 +369,78 @@ def test_regrown_columns_are_uniform_over_structural_zeros(orc):
     chi2 = ((counts - total / d) ** 2 / (total / d)).sum()
     # 63 degrees of freedom: mean 63, sd 11.2; 130 is beyond 6 sd
     assert chi2 < 130, chi2
+
+
+# ---------------------------------------------------------------- prediction and P@k (Section 2)
+
+def _read_patk_example():
+    rows = {"scores": [], "targets": [], "top": [], "hits": [], "patk": []}
+    with open(os.path.join(GOLDEN, "precision_at_k_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            rows[key].append(vals)
+    return rows
+
+
+def test_topk_and_precision_worked_example(orc):
+    ex = _read_patk_example()
+    scores = np.array(ex["scores"], np.float32)
+    off = np.zeros(len(ex["targets"]) + 1, np.int64)
+    off[1:] = np.cumsum([len(t) for t in ex["targets"]])
+    lab = np.array([int(v) for t in ex["targets"] for v in t], np.int32)
+    top, val = orc.topk(scores, 3)
+    assert top.tolist() == [[int(v) for v in r] for r in ex["top"]]
+    assert np.array_equal(val, np.take_along_axis(scores, top.astype(np.int64), 1))
+    hits = orc.precision_hits(top, off, lab)
+    assert hits.tolist() == [int(v) for v in ex["hits"][0]]
+    patk = [hits[:k].sum() / (k * 3) for k in (1, 2, 3)]
+    assert np.allclose(patk, [float(v) for v in ex["patk"][0]], rtol=0, atol=1e-15)
+
+
+def test_topk_matches_stable_sort_with_ties(orc):
+    # small integer scores force many ties; a stable sort of the negated scores lists equal scores by label
+    g = np.random.default_rng(5)
+    scores = g.integers(-4, 5, size=(7, 300)).astype(np.float32)
+    scores[scores == 0] *= g.choice([-1.0, 1.0], size=(scores == 0).sum()).astype(np.float32)  # mix -0 / +0
+    top, val = orc.topk(scores, 17)
+    ref = np.argsort(-scores.astype(np.float64), axis=1, kind="stable")[:, :17]
+    assert np.array_equal(top, ref.astype(np.int32))
+    assert np.array_equal(val.view(np.uint32), np.take_along_axis(scores, ref, 1).view(np.uint32))
+
+
+def test_topk_closed_forms(orc):
+    m = 1000
+    j = np.arange(m, dtype=np.float32)
+    # a peak at label c: the order is c, c-1, c+1, c-2, ... (the left neighbour first: smaller label)
+    c = 400
+    top, _ = orc.topk((-np.abs(j - c))[None, :].copy(), 5)
+    assert top[0].tolist() == [400, 399, 401, 398, 402]
+    # kk = m returns a permutation sorted by score; an increasing row reverses
+    top, val = orc.topk(j[None, :].copy(), m)
+    assert top[0].tolist() == list(range(m - 1, -1, -1))
+    # infinities are ordinary scores
+    z = np.zeros((1, 8), np.float32); z[0, 3] = np.inf; z[0, 5] = -np.inf
+    top, _ = orc.topk(z, 8)
+    assert top[0].tolist() == [3, 0, 1, 2, 4, 6, 7, 5]
+
+
+def test_precision_hits_closed_forms(orc):
+    # a predictor that lists an instance's own targets first scores min(k, n_targets)/k
+    b, m, kk = 6, 50, 5
+    g = np.random.default_rng(9)
+    counts = [0, 1, 2, 3, 5, 8]
+    off = np.zeros(b + 1, np.int64); off[1:] = np.cumsum(counts)
+    lab = np.concatenate([g.choice(m, n, replace=False) for n in counts]).astype(np.int32)
+    top = np.empty((b, kk), np.int32)
+    for i in range(b):
+        own = lab[off[i]:off[i + 1]].tolist()
+        rest = [q for q in range(m) if q not in own]
+        top[i] = (own + rest)[:kk]
+    hits = orc.precision_hits(top, off, lab)
+    assert hits.tolist() == [sum(1 for n in counts if n > r) for r in range(kk)]
+    # repeats in the target list count once; predictions that are no targets count nothing
+    off2 = np.array([0, 3], np.int64); lab2 = np.array([7, 7, 7], np.int32)
+    assert orc.precision_hits(np.array([[7, 8, 9]], np.int32), off2, lab2).tolist() == [1, 0, 0]
