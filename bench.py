@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--sqh-sweep", action="store_true",
                     help="also time the squared-hinge loss and the two backward calls on gradients with "
                          "0 / 90 / 99 / 99.9 %% exact zeros (implicit negative mining, Section 3.3)")
+    ap.add_argument("--predict", action="store_true",
+                    help="also time prediction (Section 2): top-5 labels of every score row and the P@k hit counts")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (FETCH+WRITE, scaled)")
     args = ap.parse_args()
@@ -251,6 +253,28 @@ def main():
                 "backward_input_ms": round(timed(lambda: L.backward_input(gbuf, idx, W, gx, b)), 4)}
         res["sqh_zero_skipping"] = sweep
         del gbuf
+    if args.predict:
+        kk = 5
+        L.forward(xs[0], idx, W, out, b)
+        top_lab = torch.empty((b, kk), dtype=torch.int32, device=dev)
+        top_val = torch.empty((b, kk), dtype=torch.float32, device=dev)
+        hits = torch.empty((kk,), dtype=torch.int64, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = 10
+        L.topk(out, b, kk, top_lab, top_val)
+        ev[0].record(stream)
+        for _ in range(reps):
+            L.topk(out, b, kk, top_lab, top_val)
+        ev[1].record(stream)
+        for _ in range(reps):
+            L.precision_hits(top_lab, tg[0][0], tg[0][1], b, kk, hits)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        t_top = ev[0].elapsed_time(ev[1]) / reps
+        res["predict"] = {"kk": kk, "topk_ms": round(t_top, 4),
+                          "topk_GBps": round(4.0 * b * m / (t_top * 1e-3) / 1e9, 1),
+                          "precision_hits_ms": round(ev[1].elapsed_time(ev[2]) / reps, 4),
+                          "hits": hits.tolist()}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))

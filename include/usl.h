@@ -99,6 +99,21 @@ usl_status usl_sqh_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_
                              const int32_t* tgt_lab, float scale, float* g, float* loss,
                              int32_t b);
 
+/* Prediction (Section 2: the k highest-scoring labels are predicted positive).  For every instance
+ * i < b, top_lab[i][r] and top_val[i][r] = out[i][top_lab[i][r]], r < kk, list the kk best labels of
+ * row i of out[b][m], best first.  Label p ranks before q if out[i][p] > out[i][q], or the two scores
+ * compare equal (-0 and +0 do) and p < q.  Scores must not be NaN.  1 <= kk <= min(m, 32).
+ * top_lab [b][kk] int32, top_val [b][kk] float32, device memory, overwritten. */
+usl_status usl_topk(usl_ctx* ctx, const float* out, int32_t b, int32_t kk, int32_t* top_lab,
+                    float* top_val);
+
+/* Precision at k (Section 2, the equation defining P@k = (1/k) sum_j y_j yhat_j): hits[r], r < kk,
+ * is set to the number of instances i < b whose rank-r prediction top_lab[i][r] is one of the
+ * instance's targets (a set: repeats count once), so P@k = (hits[0]+...+hits[k-1]) / (k*b) for every
+ * k <= kk.  top_lab [b][kk] and hits [kk] (int64) are device memory; 1 <= kk <= 64. */
+usl_status usl_precision_hits(usl_ctx* ctx, const int32_t* top_lab, const int64_t* tgt_off,
+                              const int32_t* tgt_lab, int32_t b, int32_t kk, int64_t* hits);
+
 /* Gradient of the connection values (Section 3.3, Algorithm 3):
  * grad_W[j][t] = sum_i g[i][j] * x[i][idx[j][t]].  grad_W is overwritten. */
 usl_status usl_backward_weight(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx,

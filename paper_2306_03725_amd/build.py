@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libusl.so")
 SOURCES = ["usl_api.hip", "k_products.hip", "k_elementwise.hip", "k_backward_input.hip",
-           "k_redistribute.hip", "k_schedule.hip"]
+           "k_redistribute.hip", "k_schedule.hip", "k_predict.hip"]
 # -packed-fp32-ops: packed FP32 VALU instructions are switched off (they have produced wrong
 # results on the test machines); -munsafe-fp-atomics: hardware float atomic add, no CAS loop.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

@@ -30,7 +30,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->csc_w, c->gT, c->gxT, c->nz_flags,
-                        c->slot_order};
+                        c->slot_order, c->topk_cand};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
@@ -143,6 +143,29 @@ extern "C" usl_status usl_sqh_loss_grad(usl_ctx* c, const float* out, const int6
     USL_TRY(check_batch(c, b));
     USL_TRY(usl_prepare_device(c));
     return usl_launch_loss(c, 1, out, tgt_off, tgt_lab, scale, g, loss, b);
+}
+
+extern "C" usl_status usl_topk(usl_ctx* c, const float* out, int32_t b, int32_t kk, int32_t* top_lab,
+                               float* top_val) {
+    if (!c) return USL_EINVAL;
+    NEED(out); NEED(top_lab); NEED(top_val);
+    USL_TRY(check_batch(c, b));
+    if (kk < 1) USL_FAIL(c, USL_EINVAL, "kk = %d, must be at least 1", kk);
+    if (kk > c->m || kk > usl_topk_max())
+        USL_FAIL(c, USL_ESHAPE, "kk = %d, this build takes at most min(m, %d)", kk, usl_topk_max());
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_topk(c, out, b, kk, top_lab, top_val);
+}
+
+extern "C" usl_status usl_precision_hits(usl_ctx* c, const int32_t* top_lab, const int64_t* tgt_off,
+                                         const int32_t* tgt_lab, int32_t b, int32_t kk, int64_t* hits) {
+    if (!c) return USL_EINVAL;
+    NEED(top_lab); NEED(tgt_off); NEED(tgt_lab); NEED(hits);
+    USL_TRY(check_batch(c, b));
+    if (kk < 1) USL_FAIL(c, USL_EINVAL, "kk = %d, must be at least 1", kk);
+    if (kk > 64) USL_FAIL(c, USL_ESHAPE, "kk = %d, this build counts at most 64 ranks", kk);
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_precision_hits(c, top_lab, tgt_off, tgt_lab, b, kk, hits);
 }
 
 extern "C" usl_status usl_backward_weight(usl_ctx* c, const float* g, const void* x,

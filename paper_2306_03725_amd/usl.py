@@ -17,6 +17,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 # every symbol include/usl.h declares
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
+           "usl_topk", "usl_precision_hits",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
 
@@ -37,6 +38,8 @@ _sig = {
     "usl_forward": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
+    "usl_topk": [_vp, _vp, _i32, _i32, _vp, _vp],
+    "usl_precision_hits": [_vp, _vp, _vp, _vp, _i32, _i32, _vp],
     "usl_backward_weight": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_backward_input": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32],
@@ -117,6 +120,13 @@ class Layer:
     def sqh_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
         self._ck(_lib.usl_sqh_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
                                         _ptr(g), _ptr(loss), b))
+
+    def topk(self, out, b, kk, top_lab, top_val):
+        self._ck(_lib.usl_topk(self._h, _ptr(out), b, kk, _ptr(top_lab), _ptr(top_val)))
+
+    def precision_hits(self, top_lab, tgt_off, tgt_lab, b, kk, hits):
+        self._ck(_lib.usl_precision_hits(self._h, _ptr(top_lab), _ptr(tgt_off), _ptr(tgt_lab), b, kk,
+                                         _ptr(hits)))
 
     def backward_weight(self, g, x, idx, grad_W, b):
         self._ck(_lib.usl_backward_weight(self._h, _ptr(g), _ptr(x), _ptr(idx), _ptr(grad_W), b))

@@ -123,3 +123,20 @@ def test_large_wide_full_size(orc):
 
 def test_stress_full_size(orc):
     run_full(wl.CONFIGS["stress"], orc, full_loss=False, n_lab=1024, n_inst=2)
+
+
+def test_large_topk_full_rows(orc):
+    """Top-5 over all 256 rows of Large-sized scores (the oracle walks every row in full)."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    cfg = wl.CONFIGS["large"]
+    m, b, kk = cfg.m, cfg.b, 5
+    print("full-size topk", m, b, kk, flush=True)
+    out = torch.randn((b, m), device="cuda", generator=torch.Generator("cuda").manual_seed(77))
+    out[:, ::1000] = 2.5                                     # ties among the candidates
+    L = usl.Layer(m, cfg.d, cfg.k, b)
+    lab, val = gu.empty((b, kk), torch.int32), gu.empty((b, kk))
+    L.topk(out, b, kk, lab, val)
+    ref_lab, ref_val = orc.topk(gu.host(out), kk)
+    np.testing.assert_array_equal(gu.host(lab), ref_lab)
+    np.testing.assert_array_equal(gu.host(val), ref_val)
