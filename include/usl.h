@@ -125,6 +125,25 @@ usl_status usl_backward_weight(usl_ctx* ctx, const float* g, const void* x, cons
 usl_status usl_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx, const void* W,
                               float* grad_x, int32_t b);
 
+/* The three products restricted to a list of labels (Section 6, outlook: with the uniform format, scoring a
+ * subset of labels, e.g. sampled negatives, is a slicing of the [m][k] arrays).  rows[n_rows]: int32
+ * label ids in [0, m), device memory, any order, repeats allowed (each occurrence is its own row):
+ *   out_rows   [b][n_rows]   out_rows[i][q]   = sum_t W[rows[q]][t] * x[i][idx[rows[q]][t]]
+ *   grad_W_rows[n_rows][k]   grad_W_rows[q][t] = sum_i g_rows[i][q] * x[i][idx[rows[q]][t]]
+ *   grad_x     [b][d]        grad_x[i][c]     = sum over (q,t) with idx[rows[q]][t] == c of
+ *                                               W[rows[q]][t] * g_rows[i][q]       (overwritten)
+ * g_rows is [b][n_rows].  1 <= n_rows, n_rows*k < 2^32.  The library copies the named rows of idx / W
+ * into scratch on every call; scratch is sized by n_rows, so a run of calls with the same n_rows is
+ * the fast case (a change of n_rows reallocates and waits for the stream). */
+usl_status usl_forward_rows(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W,
+                            const int32_t* rows, int64_t n_rows, float* out_rows, int32_t b);
+usl_status usl_backward_weight_rows(usl_ctx* ctx, const float* g_rows, const void* x,
+                                    const int32_t* idx, const int32_t* rows, int64_t n_rows,
+                                    float* grad_W_rows, int32_t b);
+usl_status usl_backward_input_rows(usl_ctx* ctx, const float* g_rows, const int32_t* idx,
+                                   const void* W, const int32_t* rows, int64_t n_rows,
+                                   float* grad_x, int32_t b);
+
 /* Adam (the optimizer of Section 4.1; update rule of Kingma & Ba, Algorithm 1) on the m*k
  * connection values, t = 1-based step number:
  *   m1 <- beta1*m1 + (1-beta1)*gW;  m2 <- beta2*m2 + (1-beta2)*gW^2

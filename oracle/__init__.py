@@ -123,6 +123,22 @@ def sqh_loss_grad(out, tgt_off, tgt_lab, scale):
     return loss.value, g
 
 
+def forward_rows(x, idx, W, rows):
+    """Scores of the labels listed in rows only (Section 6, outlook: a label subset is a slicing of
+    the [m][k] arrays): out_rows[i][q] = sum_t W[rows[q]][t] * x[i][idx[rows[q]][t]]."""
+    return forward(x, np.ascontiguousarray(idx[rows]), np.ascontiguousarray(W[rows]))
+
+
+def backward_weight_rows(g_rows, x, idx, rows):
+    """grad_W of the listed labels: [len(rows)][k]."""
+    return backward_weight(g_rows, x, np.ascontiguousarray(idx[rows]))
+
+
+def backward_input_rows(g_rows, idx, W, rows, d):
+    """grad_x contributed by the listed labels only."""
+    return backward_input(g_rows, np.ascontiguousarray(idx[rows]), np.ascontiguousarray(W[rows]), d)
+
+
 def topk(out, kk):
     """The kk best labels of every row, best first (ties: smaller label); returns (labels, scores)."""
     _chk(out, np.float32)

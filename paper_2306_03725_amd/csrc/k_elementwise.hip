@@ -221,3 +221,34 @@ usl_status usl_launch_adam(usl_ctx* c, void* W, const float* grad_W, float* m1, 
                            (uint16_t*)W, grad_W, m1, m2, n, lr, beta1, beta2, eps, inv_c1, inv_c2);
     return usl_check_launch(c, "adam");
 }
+
+// ---- rows of idx / W picked by a list of label ids (label-subset calls) ----------------------
+namespace {
+template <typename TS>
+__global__ void __launch_bounds__(256)
+k_gather_rows(const int32_t* __restrict__ idx, const TS* __restrict__ W, const int32_t* __restrict__ rows,
+              int64_t n, int64_t m, int k, int32_t* __restrict__ dst_idx, TS* __restrict__ dst_W) {
+    const int64_t total = n * k;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t q = e / k;
+        const int t = (int)(e - q * k);
+        int64_t j = rows[q];
+        j = j < 0 ? 0 : (j >= m ? m - 1 : j);
+        dst_idx[e] = idx[j * k + t];
+        if (W) dst_W[e] = W[j * k + t];
+    }
+}
+}  // namespace
+
+usl_status usl_launch_gather_rows(usl_ctx* c, const int32_t* idx, const void* W, const int32_t* rows,
+                                  int64_t n, int32_t* dst_idx, void* dst_W) {
+    int64_t blocks = (n * c->k + 255) / 256;
+    if (blocks > (int64_t)c->num_cu * 32) blocks = (int64_t)c->num_cu * 32;
+    if (c->storage == USL_F32)
+        hipLaunchKernelGGL(k_gather_rows<float>, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx,
+                           (const float*)W, rows, n, c->m, c->k, dst_idx, (float*)dst_W);
+    else
+        hipLaunchKernelGGL(k_gather_rows<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream, idx,
+                           (const uint16_t*)W, rows, n, c->m, c->k, dst_idx, (uint16_t*)dst_W);
+    return usl_check_launch(c, "gather_rows");
+}

@@ -27,10 +27,11 @@ extern "C" usl_status usl_create(usl_ctx** out, int64_t m, int32_t d, int32_t k,
 
 extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (!c) return USL_OK;
+    (void)usl_destroy(c->sub);
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label, c->csc_w, c->gT, c->gxT, c->nz_flags,
-                        c->slot_order, c->topk_cand};
+                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
@@ -184,6 +185,78 @@ extern "C" usl_status usl_backward_input(usl_ctx* c, const float* g, const int32
     USL_TRY(check_batch(c, b));
     USL_TRY(usl_prepare_device(c));
     return usl_launch_backward_input(c, g, idx, W, grad_x, b);
+}
+
+// ---- label-subset calls: the rows named by `rows` are copied out and run through the same kernels
+// in a child context whose m is the subset size.
+
+static usl_status subset_context(usl_ctx* c, int64_t n, const int32_t* idx, const void* W,
+                                 const int32_t* rows, bool need_W, usl_ctx** child) {
+    if (n < 1) USL_FAIL(c, USL_EINVAL, "n_rows = %lld < 1", (long long)n);
+    if (n > 0x7FFFFFFFll || n * (int64_t)c->k >= (int64_t)1 << 32)
+        USL_FAIL(c, USL_ESHAPE, "n_rows = %lld is too large", (long long)n);
+    USL_TRY(usl_prepare_device(c));
+    if (c->sub && c->sub->m != n) {   // scratch is sized by m: a new subset size starts afresh
+        USL_TRY(usl_destroy(c->sub));
+        c->sub = nullptr;
+    }
+    if (!c->sub) {
+        usl_status s = usl_create(&c->sub, n, c->d, c->k, c->max_b, (usl_dtype)c->storage, c->stream);
+        if (s != USL_OK) USL_FAIL(c, s, "could not create the context of a %lld-label subset", (long long)n);
+    }
+    usl_ctx* sub = c->sub;
+    sub->stream = c->stream;
+    usl_status s = usl_prepare_device(sub);
+    if (s != USL_OK) USL_FAIL(c, s, "%s", sub->err);
+    sub->csc_built_for = nullptr;    // same scratch pointer, new contents
+    sub->slot_order_for = nullptr;
+    const size_t esize = c->storage == USL_F32 ? 4 : 2;
+    USL_TRY(usl_reserve(c, (void**)&c->sub_idx, &c->sub_idx_cap, (size_t)n * c->k * 4));
+    if (need_W) USL_TRY(usl_reserve(c, &c->sub_W, &c->sub_W_cap, (size_t)n * c->k * esize));
+    USL_TRY(usl_launch_gather_rows(c, idx, need_W ? W : nullptr, rows, n, c->sub_idx, need_W ? c->sub_W : nullptr));
+    *child = sub;
+    return USL_OK;
+}
+
+#define SUB_TRY(expr)                                             \
+    do {                                                          \
+        usl_status s_ = (expr);                                   \
+        if (s_ != USL_OK) USL_FAIL(c, s_, "%s", sub->err);        \
+    } while (0)
+
+extern "C" usl_status usl_forward_rows(usl_ctx* c, const void* x, const int32_t* idx, const void* W,
+                                       const int32_t* rows, int64_t n_rows, float* out_rows, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(x); NEED(idx); NEED(W); NEED(rows); NEED(out_rows);
+    USL_TRY(check_batch(c, b));
+    usl_ctx* sub = nullptr;
+    USL_TRY(subset_context(c, n_rows, idx, W, rows, true, &sub));
+    SUB_TRY(usl_launch_forward(sub, x, c->sub_idx, c->sub_W, out_rows, b));
+    return USL_OK;
+}
+
+extern "C" usl_status usl_backward_weight_rows(usl_ctx* c, const float* g_rows, const void* x,
+                                               const int32_t* idx, const int32_t* rows, int64_t n_rows,
+                                               float* grad_W_rows, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(g_rows); NEED(x); NEED(idx); NEED(rows); NEED(grad_W_rows);
+    USL_TRY(check_batch(c, b));
+    usl_ctx* sub = nullptr;
+    USL_TRY(subset_context(c, n_rows, idx, nullptr, rows, false, &sub));
+    SUB_TRY(usl_launch_backward_weight(sub, g_rows, x, c->sub_idx, grad_W_rows, b));
+    return USL_OK;
+}
+
+extern "C" usl_status usl_backward_input_rows(usl_ctx* c, const float* g_rows, const int32_t* idx,
+                                              const void* W, const int32_t* rows, int64_t n_rows,
+                                              float* grad_x, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(g_rows); NEED(idx); NEED(W); NEED(rows); NEED(grad_x);
+    USL_TRY(check_batch(c, b));
+    usl_ctx* sub = nullptr;
+    USL_TRY(subset_context(c, n_rows, idx, W, rows, true, &sub));
+    SUB_TRY(usl_launch_backward_input(sub, g_rows, c->sub_idx, c->sub_W, grad_x, b));
+    return USL_OK;
 }
 
 extern "C" usl_status usl_adam_step(usl_ctx* c, void* W, const float* grad_W, float* m1, float* m2,

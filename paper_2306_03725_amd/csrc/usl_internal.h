@@ -39,6 +39,10 @@ struct usl_ctx {
     const int32_t* slot_order_for; // idx pointer it was computed from (NULL = stale)
     float* gT;                size_t gT_cap;   // [tiles][m][32] upstream gradient, one 128-byte piece per (tile of 32 instances, label)
     uint8_t* nz_flags;        size_t nz_flags_cap;   // [tiles][m] 1 = that 32-instance piece of gT is not all zero
+    // label-subset calls: a child context sized for the subset, and the subset's rows of idx / W
+    usl_ctx* sub;
+    int32_t* sub_idx;         size_t sub_idx_cap;
+    void* sub_W;              size_t sub_W_cap;
     uint64_t* topk_cand;      size_t topk_cand_cap;  // [b][segments][kk] packed (score, label) keys
     float* gxT;               size_t gxT_cap;  // [tiles][d][32] input gradient in the same layout
 };
@@ -90,7 +94,10 @@ usl_status usl_launch_topk(usl_ctx* ctx, const float* out, int32_t b, int32_t kk
                            float* top_val);
 usl_status usl_launch_precision_hits(usl_ctx* ctx, const int32_t* top_lab, const int64_t* tgt_off,
                                      const int32_t* tgt_lab, int32_t b, int32_t kk, int64_t* hits);
-int usl_topk_max(void);  // largest kk usl_launch_topk takes
+int usl_topk_max(void);
+// dst_idx[q][:] = idx[rows[q]][:] and (if W) dst_W[q][:] = W[rows[q]][:], q < n; row ids are clamped into [0, m)
+usl_status usl_launch_gather_rows(usl_ctx* ctx, const int32_t* idx, const void* W, const int32_t* rows,
+                                  int64_t n, int32_t* dst_idx, void* dst_W);  // largest kk usl_launch_topk takes
 usl_status usl_launch_validate(usl_ctx* ctx, const int32_t* idx, int64_t* n_bad_host);
 usl_status usl_launch_philox(usl_ctx* ctx, const uint32_t* ctr, uint32_t key0, uint32_t key1,
                              uint32_t* out, int64_t n);

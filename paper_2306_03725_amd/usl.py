@@ -18,6 +18,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
            "usl_topk", "usl_precision_hits",
+           "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
 
@@ -39,6 +40,9 @@ _sig = {
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_topk": [_vp, _vp, _i32, _i32, _vp, _vp],
+    "usl_forward_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
+    "usl_backward_weight_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
+    "usl_backward_input_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
     "usl_precision_hits": [_vp, _vp, _vp, _vp, _i32, _i32, _vp],
     "usl_backward_weight": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_backward_input": [_vp, _vp, _vp, _vp, _vp, _i32],
@@ -120,6 +124,18 @@ class Layer:
     def sqh_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
         self._ck(_lib.usl_sqh_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
                                         _ptr(g), _ptr(loss), b))
+
+    def forward_rows(self, x, idx, W, rows, n_rows, out_rows, b):
+        self._ck(_lib.usl_forward_rows(self._h, _ptr(x), _ptr(idx), _ptr(W), _ptr(rows), n_rows,
+                                       _ptr(out_rows), b))
+
+    def backward_weight_rows(self, g_rows, x, idx, rows, n_rows, grad_W_rows, b):
+        self._ck(_lib.usl_backward_weight_rows(self._h, _ptr(g_rows), _ptr(x), _ptr(idx), _ptr(rows), n_rows,
+                                               _ptr(grad_W_rows), b))
+
+    def backward_input_rows(self, g_rows, idx, W, rows, n_rows, grad_x, b):
+        self._ck(_lib.usl_backward_input_rows(self._h, _ptr(g_rows), _ptr(idx), _ptr(W), _ptr(rows), n_rows,
+                                              _ptr(grad_x), b))
 
     def topk(self, out, b, kk, top_lab, top_val):
         self._ck(_lib.usl_topk(self._h, _ptr(out), b, kk, _ptr(top_lab), _ptr(top_val)))

@@ -444,3 +444,28 @@ def test_precision_hits_closed_forms(orc):
     # repeats in the target list count once; predictions that are no targets count nothing
     off2 = np.array([0, 3], np.int64); lab2 = np.array([7, 7, 7], np.int32)
     assert orc.precision_hits(np.array([[7, 8, 9]], np.int32), off2, lab2).tolist() == [1, 0, 0]
+
+
+# ---------------------------------------------------------------- label subsets (Section 6, outlook)
+
+def test_label_subset_products_are_slices_of_the_full_products(orc):
+    cfg = wl.custom(300, 90, 8, 6, index=71)
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    r = wl.rng(cfg, 3)
+    rows = r.choice(cfg.m, size=57, replace=True).astype(np.int64)          # with repeats, unsorted
+    # forward: the listed columns of the full score matrix, bit for bit
+    full = orc.forward(x, idx, W)
+    np.testing.assert_array_equal(orc.forward_rows(x, idx, W, rows), full[:, rows])
+    # backward: the same as the full backward calls on a gradient that is zero off the listed labels
+    rows_u = np.unique(rows)
+    g_rows = r.standard_normal((cfg.b, len(rows_u))).astype(np.float32)
+    g_full = np.zeros((cfg.b, cfg.m), np.float32)
+    g_full[:, rows_u] = g_rows
+    np.testing.assert_array_equal(orc.backward_weight_rows(g_rows, x, idx, rows_u),
+                                  orc.backward_weight(g_full, x, idx)[rows_u])
+    np.testing.assert_array_equal(orc.backward_input_rows(g_rows, idx, W, rows_u, cfg.d),
+                                  orc.backward_input(g_full, idx, W, cfg.d))
+    # and against the dense matrix the format stands for (numpy matmul in float64)
+    dense = scatter_dense(idx, W, cfg.d)                                     # [m][d]
+    ref = x.astype(np.float64) @ dense[rows].T
+    assert_close(orc.forward_rows(x, idx, W, rows), ref, 1e-6, "subset scores vs dense")
