@@ -152,6 +152,20 @@ usl_status usl_backward_input_rows(usl_ctx* ctx, const float* g_rows, const int3
 usl_status usl_adam_step(usl_ctx* ctx, void* W, const float* grad_W, float* m1, float* m2,
                          int64_t t, float lr, float beta1, float beta2, float eps);
 
+/* One training step of the layer in one call: usl_forward, the loss (loss_kind 0 = binary
+ * cross-entropy, 1 = squared hinge), usl_backward_weight, usl_backward_input and usl_adam_step, in that
+ * order (Sections 3.2-3.3, 4.1), with the same arguments and the same results as the separate calls
+ * (the loss value up to the order of its additions).  Fused inside: the loss writes the gradient in the
+ * two layouts the backward products read, so no separate transposition pass runs.
+ *   g      [b][m] float32  work and result: the scores, then the upstream gradient
+ *   grad_W [m][k] float32  result: the gradient Adam consumed
+ *   grad_x [b][d] float32  result, or NULL to skip the input gradient
+ * W, m1, m2 are updated in place; grad_x is computed from W as it was before the update. */
+usl_status usl_train_step(usl_ctx* ctx, const void* x, const int32_t* idx, void* W, float* m1, float* m2,
+                          const int64_t* tgt_off, const int32_t* tgt_lab, int32_t loss_kind, float scale,
+                          int64_t t, float lr, float beta1, float beta2, float eps, float* g,
+                          float* grad_W, float* grad_x, float* loss, int32_t b);
+
 /* Connection redistribution (Section 2: the prune / redistribute cycle of SET; Section 3.2:
  * a column's slots never move).  In place:
  *   1. n = floor(fraction * m*k) connections with the smallest magnitude in the whole layer are

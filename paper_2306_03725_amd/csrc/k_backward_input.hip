@@ -389,15 +389,28 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
 
 }  // namespace
 
-usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
-                                     float* grad_x, int32_t b) {
+// Lists for this idx, and the scratch a call with batch b needs; clears the nonzero-piece counter.
+usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
     if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) USL_TRY(build_csc(c, idx));
+    const int ntile = (b + 31) / 32;
+    USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)ntile * c->m * 32 * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)ntile * c->d * 32 * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
+    if (!c->counter64) {
+        size_t cap = 0;
+        USL_TRY(usl_reserve(c, (void**)&c->counter64, &cap, 64));
+    }
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, usl_nz_cells(c), (size_t)1);
+    return usl_check_launch(c, "backward_input scratch");
+}
+
+// The gathers, once gT, the piece flags and the sampled count of nonzero pieces are in place.
+// sampled_labels = how many labels the count covers (per tile).
+usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels) {
     const size_t N = (size_t)c->m * c->k;
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
     const int ntile = (b + 31) / 32;
-    USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)ntile * c->m * 32 * 4));
-    USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)ntile * c->d * 32 * 4));
     {   // weights in list order
         size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
         if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
@@ -408,20 +421,7 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
                                (const uint16_t*)W, c->csc_slot, N, c->csc_w);
     }
-    USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
-    if (!c->counter64) {
-        size_t cap = 0;
-        USL_TRY(usl_reserve(c, (void**)&c->counter64, &cap, 64));
-    }
-    uint32_t* nz_cells = reinterpret_cast<uint32_t*>(c->counter64) + 4;
-    {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
-        hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, nz_cells, (size_t)1);
-        dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)ntile);
-        hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
-                           c->nz_flags, nz_cells);
-    }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
-    const uint64_t sampled_labels = (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32;
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
     const uint32_t sparse_below = (uint32_t)(cells / 2 > 0xFFFFFFFFull ? 0xFFFFFFFFull : cells / 2);
     {
@@ -429,11 +429,22 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
         for (int w = 0; w < nwin; ++w)
             hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
                                c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d,
-                               w > 0 ? 1 : 0, c->nz_flags, c->m, nz_cells, sparse_below);
+                               w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
     }
     {
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
         hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d);
     }
     return usl_check_launch(c, "backward_input");
+}
+
+usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
+                                     float* grad_x, int32_t b) {
+    USL_TRY(usl_bwd_input_prepare(c, idx, b));
+    {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
+        dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));
+        hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
+                           c->nz_flags, usl_nz_cells(c));
+    }
+    return usl_bwd_input_run(c, W, grad_x, b, (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32);
 }

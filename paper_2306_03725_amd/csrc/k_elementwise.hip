@@ -103,6 +103,94 @@ k_bce(const float* out, const int64_t* __restrict__ tgt_off, const int32_t* __re
     }
 }
 
+// The same loss, tile by tile, for a caller that wants the gradient twice: in place over the scores
+// (row-major, for backward-weight) and as gT[tile][label][32] with the piece flags (for backward-input),
+// which saves the separate transposition pass.  grid (blocks of LT_TL labels, tiles of 32 instances).
+constexpr int LT_TL = 128;
+constexpr int LT_SAMPLE = 16;   // one label block in 16 feeds the nonzero-piece count
+
+template <bool VEC, int LOSS>
+__global__ void __launch_bounds__(256)
+k_loss_tiles(float* zg, const int64_t* __restrict__ tgt_off, const int32_t* __restrict__ tgt_lab, float scale,
+             double* __restrict__ partials, int64_t m, int b, float* __restrict__ gT,
+             uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells) {
+    __shared__ float tile[32][LT_TL + 1];
+    __shared__ uint32_t ybits[32][LT_TL / 32];
+    __shared__ double red[4];
+    __shared__ uint32_t block_cells;
+    const int tid = threadIdx.x;
+    const int i0 = blockIdx.y * 32;
+    const int64_t j0 = (int64_t)blockIdx.x * LT_TL;
+    const int nl = (int)min((int64_t)LT_TL, m - j0);
+    if (tid < 32 * (LT_TL / 32)) (&ybits[0][0])[tid] = 0u;
+    if (tid == 0) block_cells = 0;
+    __syncthreads();
+    {   // 8 lanes walk the target list of one instance
+        const int ii = tid >> 3, i = i0 + ii;
+        if (i < b)
+            for (int64_t p = tgt_off[i] + (tid & 7); p < tgt_off[i + 1]; p += 8) {
+                const int64_t rel = (int64_t)tgt_lab[p] - j0;
+                if (rel >= 0 && rel < nl) atomicOr(&ybits[ii][rel >> 5], 1u << (rel & 31));
+            }
+    }
+    __syncthreads();
+    float lsum = 0.f;
+    if (VEC) {   // m % 4 == 0 and 16-byte aligned rows: nl is a multiple of 4
+        const int c4 = (tid & 31) * 4;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int ii = pass * 8 + (tid >> 5), i = i0 + ii;
+            float4 gv = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < b && c4 < nl) {
+                float4* p = reinterpret_cast<float4*>(zg + (size_t)i * m + j0 + c4);
+                const float4 z = *p;
+                const uint32_t yb = ybits[ii][c4 >> 5] >> (c4 & 31);
+                const Bce1 a = bce_one<LOSS>(z.x, (float)(yb & 1u), scale), b2 = bce_one<LOSS>(z.y, (float)((yb >> 1) & 1u), scale),
+                           c = bce_one<LOSS>(z.z, (float)((yb >> 2) & 1u), scale), dd = bce_one<LOSS>(z.w, (float)((yb >> 3) & 1u), scale);
+                gv = make_float4(a.g, b2.g, c.g, dd.g);
+                *p = gv;
+                lsum += (a.l + b2.l) + (c.l + dd.l);
+            }
+            tile[ii][c4] = gv.x; tile[ii][c4 + 1] = gv.y; tile[ii][c4 + 2] = gv.z; tile[ii][c4 + 3] = gv.w;
+        }
+    } else {
+        const int cc = tid & (LT_TL - 1);
+#pragma unroll 4
+        for (int pass = 0; pass < 16; ++pass) {
+            const int ii = pass * 2 + (tid >> 7), i = i0 + ii;
+            float gv = 0.f;
+            if (i < b && cc < nl) {
+                float* p = zg + (size_t)i * m + j0 + cc;
+                const Bce1 a = bce_one<LOSS>(*p, (float)((ybits[ii][cc >> 5] >> (cc & 31)) & 1u), scale);
+                gv = a.g;
+                *p = gv;
+                lsum += a.l;
+            }
+            tile[ii][cc] = gv;
+        }
+    }
+    __syncthreads();
+    {   // the tile's pieces are one contiguous run of gT: nl * 32 floats
+        float* dst = gT + ((size_t)blockIdx.y * m + j0) * 32;
+        for (int e = tid; e < nl * 32; e += 256) dst[e] = tile[e & 31][e >> 5];
+        if (tid < nl) {
+            bool any = false;
+#pragma unroll 8
+            for (int ii = 0; ii < 32; ++ii) any |= tile[ii][tid] != 0.f;
+            nzf[(size_t)blockIdx.y * m + j0 + tid] = any ? 1 : 0;
+            if ((blockIdx.x % LT_SAMPLE) == 0 && any) atomicAdd(&block_cells, 1u);
+        }
+    }
+    double v = (double)lsum;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    if (tid == 0) {
+        partials[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+        if ((blockIdx.x % LT_SAMPLE) == 0 && block_cells) atomicAdd(nz_cells, block_cells);
+    }
+}
+
 // One block adds the per-block sums in a fixed order: the loss is reproducible run to run.
 __global__ void __launch_bounds__(1024)
 k_bce_finish(const double* __restrict__ partials, size_t n, float scale, float* __restrict__ loss) {
@@ -199,6 +287,29 @@ usl_status usl_launch_loss(usl_ctx* c, int loss_kind, const float* out, const in
     else                       { if (vec) USL_LOSS(true, LOSS_SQH); else USL_LOSS(false, LOSS_SQH); }
 #undef USL_LOSS
     USL_TRY(usl_check_launch(c, "loss"));
+    hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, c->bce_partials, nblk, scale, loss);
+    return usl_check_launch(c, "loss_finish");
+}
+
+usl_status usl_launch_loss_tiles(usl_ctx* c, int loss_kind, float* zg, const int64_t* tgt_off,
+                                 const int32_t* tgt_lab, float scale, float* loss, int32_t b,
+                                 uint64_t* sampled_labels) {
+    const int64_t nlb = (c->m + LT_TL - 1) / LT_TL;
+    const int ntile = (b + 31) / 32;
+    const size_t nblk = (size_t)nlb * ntile;
+    size_t cap = c->bce_partials_cap;
+    USL_TRY(usl_reserve(c, (void**)&c->bce_partials, &cap, nblk * sizeof(double)));
+    c->bce_partials_cap = cap;
+    const bool vec = (c->m % 4 == 0) && ((uintptr_t)zg % 16 == 0);
+    dim3 grid((unsigned)nlb, (unsigned)ntile);
+#define USL_LOSS(VEC, KIND)                                                                              \
+    hipLaunchKernelGGL((k_loss_tiles<VEC, KIND>), grid, dim3(256), 0, c->stream, zg, tgt_off, tgt_lab,   \
+                       scale, c->bce_partials, c->m, (int)b, c->gT, c->nz_flags, usl_nz_cells(c))
+    if (loss_kind == LOSS_BCE) { if (vec) USL_LOSS(true, LOSS_BCE); else USL_LOSS(false, LOSS_BCE); }
+    else                       { if (vec) USL_LOSS(true, LOSS_SQH); else USL_LOSS(false, LOSS_SQH); }
+#undef USL_LOSS
+    USL_TRY(usl_check_launch(c, "loss (tiles)"));
+    *sampled_labels = (uint64_t)((nlb + LT_SAMPLE - 1) / LT_SAMPLE) * LT_TL;
     hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, c->bce_partials, nblk, scale, loss);
     return usl_check_launch(c, "loss_finish");
 }

@@ -239,6 +239,9 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             const int64_t j = jme + (int64_t)l * NT;
             gnext[l] = (j < m && i_begin < i_end) ? g[(size_t)i_begin * m + j] : 0.f;
         }
+        // with a short row the flag words lie inside the buffer the indices were transposed through:
+        // every wavefront must have picked up its indices before the first flag is written
+        __syncthreads();
 #pragma unroll 1
         for (int i = i_begin; i < i_end; ++i) {
             float gv[LPT];

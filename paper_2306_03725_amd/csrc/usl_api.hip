@@ -275,6 +275,38 @@ extern "C" usl_status usl_adam_step(usl_ctx* c, void* W, const float* grad_W, fl
                            (float)(1.0 / c2));
 }
 
+extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* idx, void* W, float* m1,
+                                     float* m2, const int64_t* tgt_off, const int32_t* tgt_lab,
+                                     int32_t loss_kind, float scale, int64_t t, float lr, float beta1,
+                                     float beta2, float eps, float* g, float* grad_W, float* grad_x,
+                                     float* loss, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(x); NEED(idx); NEED(W); NEED(m1); NEED(m2); NEED(tgt_off); NEED(tgt_lab); NEED(g); NEED(grad_W);
+    NEED(loss);
+    if (loss_kind != 0 && loss_kind != 1) USL_FAIL(c, USL_EINVAL, "loss_kind %d is neither 0 (BCE) nor 1 (squared hinge)", loss_kind);
+    if (!(scale == scale) || isinf(scale)) USL_FAIL(c, USL_EINVAL, "scale is not finite");
+    if (t < 1) USL_FAIL(c, USL_EINVAL, "step number t = %lld < 1", (long long)t);
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        USL_FAIL(c, USL_EINVAL, "beta1, beta2 must lie in [0,1)");
+    if (!(eps >= 0.f) || !(lr == lr)) USL_FAIL(c, USL_EINVAL, "eps < 0 or lr is NaN");
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    USL_TRY(usl_launch_forward(c, x, idx, W, g, b));
+    if (grad_x) {
+        uint64_t sampled = 0;
+        USL_TRY(usl_bwd_input_prepare(c, idx, b));
+        USL_TRY(usl_launch_loss_tiles(c, loss_kind, g, tgt_off, tgt_lab, scale, loss, b, &sampled));
+        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b));
+        USL_TRY(usl_bwd_input_run(c, W, grad_x, b, sampled));
+    } else {
+        USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
+        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b));
+    }
+    const double c1 = 1.0 - pow((double)beta1, (double)t);
+    const double c2 = 1.0 - pow((double)beta2, (double)t);
+    return usl_launch_adam(c, W, grad_W, m1, m2, lr, beta1, beta2, eps, (float)(1.0 / c1), (float)(1.0 / c2));
+}
+
 extern "C" usl_status usl_redistribute(usl_ctx* c, int32_t* idx, void* W, float* m1, float* m2,
                                        double fraction, uint64_t seed, uint64_t epoch,
                                        int64_t* n_rewired_host) {

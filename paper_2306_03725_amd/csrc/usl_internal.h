@@ -81,6 +81,16 @@ usl_status usl_launch_backward_weight(usl_ctx* ctx, const float* g, const void* 
                                       const int32_t* idx, float* grad_W, int32_t b);
 usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx,
                                      const void* W, float* grad_x, int32_t b);
+// backward_input in two halves, for callers that produce gT / nz_flags / the nonzero count themselves
+usl_status usl_bwd_input_prepare(usl_ctx* ctx, const int32_t* idx, int32_t b);
+usl_status usl_bwd_input_run(usl_ctx* ctx, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels);
+static inline uint32_t* usl_nz_cells(usl_ctx* c) { return reinterpret_cast<uint32_t*>(c->counter64) + 4; }
+// Loss and gradient in place on zg[b][m], which also leaves the gradient in c->gT (tile-major) with
+// its piece flags and sampled nonzero count (usl_bwd_input_prepare must have run); *sampled_labels
+// receives the number of labels the count covers.
+usl_status usl_launch_loss_tiles(usl_ctx* ctx, int loss_kind, float* zg, const int64_t* tgt_off,
+                                 const int32_t* tgt_lab, float scale, float* loss, int32_t b,
+                                 uint64_t* sampled_labels);
 // loss_kind: 0 = binary cross-entropy, 1 = squared hinge
 usl_status usl_launch_loss(usl_ctx* ctx, int loss_kind, const float* out, const int64_t* tgt_off,
                            const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);

@@ -17,7 +17,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 # every symbol include/usl.h declares
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
-           "usl_topk", "usl_precision_hits",
+           "usl_topk", "usl_precision_hits", "usl_train_step",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
@@ -40,6 +40,8 @@ _sig = {
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_topk": [_vp, _vp, _i32, _i32, _vp, _vp],
+    "usl_train_step": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _i64, _f32, _f32, _f32, _f32,
+                       _vp, _vp, _vp, _vp, _i32],
     "usl_forward_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
     "usl_backward_weight_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
     "usl_backward_input_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
@@ -95,7 +97,7 @@ class Layer:
         self.m, self.d, self.k, self.max_b, self.storage = m, d, k, max_b, storage
 
     def close(self):
-        if self._h:
+        if self._h and _lib is not None:      # _lib is gone when the interpreter is shutting down
             _lib.usl_destroy(self._h)
             self._h = _vp()
 
@@ -153,6 +155,12 @@ class Layer:
     def adam_step(self, W, grad_W, m1, m2, t, lr, beta1, beta2, eps):
         self._ck(_lib.usl_adam_step(self._h, _ptr(W), _ptr(grad_W), _ptr(m1), _ptr(m2), t, lr,
                                     beta1, beta2, eps))
+
+    def train_step(self, x, idx, W, m1, m2, tgt_off, tgt_lab, loss_kind, scale, t, lr, beta1, beta2, eps,
+                   g, grad_W, grad_x, loss, b):
+        self._ck(_lib.usl_train_step(self._h, _ptr(x), _ptr(idx), _ptr(W), _ptr(m1), _ptr(m2), _ptr(tgt_off),
+                                     _ptr(tgt_lab), loss_kind, scale, t, lr, beta1, beta2, eps, _ptr(g),
+                                     _ptr(grad_W), _ptr(grad_x) if grad_x is not None else None, _ptr(loss), b))
 
     def redistribute(self, idx, W, m1, m2, fraction, seed, epoch):
         n = _i64(-1)
