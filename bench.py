@@ -29,7 +29,7 @@ KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
     "bce": "k_bce + k_bce_finish",
     "backward_weight": "k_backward_weight (1 launch)",
-    "backward_input": "k_gather_w + k_transpose + one k_bwd_input_window per label window + k_transpose",
+    "backward_input": "k_gather_w + k_transpose_g + one k_bwd_input_window per label window + k_untile",
     "adam": "k_adam (1 launch)",
 }
 
@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--sqh-sweep", action="store_true",
                     help="also time the squared-hinge loss and the two backward calls on gradients with "
                          "0 / 90 / 99 / 99.9 %% exact zeros (implicit negative mining, Section 3.3)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="time the step as five separate calls instead of usl_train_step")
     ap.add_argument("--predict", action="store_true",
                     help="also time prediction (Section 2): top-5 labels of every score row and the P@k hit counts")
     ap.add_argument("--traffic-kib", type=float, default=None,
@@ -159,8 +161,20 @@ def main():
         if ev is not None:
             ev.append(marks)
 
+    def fused_step():
+        state["t"] += 1
+        t = state["t"]
+        x = xs[t % len(xs)]
+        off, lab = tg[t % len(tg)]
+        L.train_step(x, idx, W, m1, m2, off, lab, 0, scale, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                     out, gW, gx, loss, b)
+        if wl.is_redistribution_step(cfg, t):
+            L.redistribute(idx, W, m1, m2, cfg.fraction, seed, state["epoch"])
+            state["epoch"] += 1
+
+    timed_step = step if args.separate_calls else fused_step
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     if args.calibrate_copy:    # 2^30 bytes read + 2^30 bytes written by one elementwise kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -169,17 +183,27 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    events = []
+    # ---- the timed region: exactly args.steps steps
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()
     e0.record(stream)
     for _ in range(args.steps):
-        step(events)
+        timed_step()
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall0) * 1e3
     total_ms = e0.elapsed_time(e1)
     loss_value = float(loss.item())
+    # ---- the same steps as separate calls with an event between the calls: the per-call breakdown
+    events = []
+    step()
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s0.record(stream)
+    for _ in range(args.steps):
+        step(events)
+    s1.record(stream)
+    torch.cuda.synchronize()
+    separate_ms = s0.elapsed_time(s1) / args.steps
     n_bad = L.validate_indices(idx)
 
     per_call = {c: [] for c in calls}
@@ -217,6 +241,10 @@ def main():
         "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
         "call_GBps": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9, 1) for c in calls[:5]},
         "wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "timed_path": ("separate calls: usl_forward, usl_bce_loss_grad, usl_backward_weight, usl_backward_input, "
+                       "usl_adam_step" if args.separate_calls else "usl_train_step (the same five stages in one call)")
+                      + ", usl_redistribute on its schedule",
+        "separate_calls_ms_per_step": round(separate_ms, 4),
         "loss": loss_value, "bad_rows": n_bad, "redistributions": state["epoch"],
         "roofline": roof,
     }
