@@ -159,14 +159,31 @@ k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_lab
     }
 }
 
-// weights in list order, as float32 (refreshed on every call: W changes with every Adam step)
+// Weights in list order, as float32 (refreshed on every call: W changes with every Adam step).  The lists of
+// one label window draw on a contiguous 16384*k slice of W; workgroups are dealt round-robin to the 8 XCDs,
+// so window = f(blockIdx % 8) keeps a slice in one XCD's L2 while its GW_BPW workgroups pick it apart.
+constexpr int GW_BPW = 32, GW_NT = 1024;
 template <typename TS>
-__global__ void __launch_bounds__(256)
-k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, size_t N,
-           float* __restrict__ wl) {
-    const size_t s = (size_t)gridDim.x * 256;
-    for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < N; p += s)
-        wl[p] = usl_load_f32<TS>(W, (size_t)slot[p]);
+__global__ void __launch_bounds__(GW_NT)
+k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const uint32_t* __restrict__ ptr,
+           int d, int nwin, float* __restrict__ wl) {
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int w = (local / GW_BPW) * 8 + xcd;
+    if (w >= nwin) return;
+    const uint32_t p0 = ptr[(size_t)w * d], p1 = ptr[(size_t)(w + 1) * d];
+    constexpr uint32_t STEP = GW_BPW * GW_NT;
+    uint32_t p = p0 + (local % GW_BPW) * GW_NT + threadIdx.x;
+    for (; p + 3 * STEP < p1; p += 4 * STEP) {
+        uint32_t e[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = slot[p + q * STEP];
+        float v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = usl_load_f32<TS>(W, (size_t)e[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) wl[p + q * STEP] = v[q];
+    }
+    for (; p < p1; p += STEP) wl[p] = usl_load_f32<TS>(W, (size_t)slot[p]);
 }
 
 // grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.x = tile, blockIdx.y = block of 32 features.
@@ -407,19 +424,17 @@ usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
 // The gathers, once gT, the piece flags and the sampled count of nonzero pieces are in place.
 // sampled_labels = how many labels the count covers (per tile).
 usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels) {
-    const size_t N = (size_t)c->m * c->k;
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
     const int ntile = (b + 31) / 32;
     {   // weights in list order
-        size_t blocks = (N + 256 * 8 - 1) / (256 * 8);
-        if (blocks > (size_t)c->num_cu * 16) blocks = (size_t)c->num_cu * 16;
+        const unsigned blocks = (unsigned)((nwin + 7) / 8) * 8 * GW_BPW;
         if (c->storage == USL_F32)
-            hipLaunchKernelGGL(k_gather_w<float>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
-                               (const float*)W, c->csc_slot, N, c->csc_w);
+            hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w);
         else
-            hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
-                               (const uint16_t*)W, c->csc_slot, N, c->csc_w);
+            hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w);
     }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
