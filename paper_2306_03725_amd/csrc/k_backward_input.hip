@@ -160,7 +160,7 @@ k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_lab
 }
 
 // Weights in list order, as float32 (refreshed on every call: W changes with every Adam step).  The lists of
-// one label window draw on a contiguous 16384*k slice of W; workgroups are dealt round-robin to the 8 XCDs,
+// one label window draw on a contiguous slice of W (window labels * k values); workgroups are dealt round-robin to the 8 XCDs,
 // so window = f(blockIdx % 8) keeps a slice in one XCD's L2 while its GW_BPW workgroups pick it apart.
 constexpr int GW_BPW = 32, GW_NT = 1024;
 template <typename TS>
@@ -294,7 +294,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             }
         }
     }
-    // Lists are short (m*k/d per feature and 16384 labels: 16 at Large), so the walk is a chain of
+    // Lists are short (window labels * k / d entries: 24 at Large), so the walk is a chain of
     // dependent load latencies, not a stream.  U entries go per trip, the tail is masked rather than
     // walked one by one, and the next trip's (label, weight) pairs are requested while this trip's
     // pieces are in flight.  The 8 lanes of a group read the same entry.
@@ -346,8 +346,9 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
 }
 
 int window_labels(const usl_ctx* c) {
-    // a window's 128-byte-per-label slice of gT should sit in one XCD's 4 MiB L2 with room to spare
-    int w = 16384;
+    // a window's 128-byte-per-label slice of gT (3 MiB here) should sit in one XCD's 4 MiB L2 with room
+    // for the list entries that stream past it; measured best at Large among 8192 ... 32768
+    int w = 24576;
     const char* e = getenv("USL_TUNE_WIN");
     if (e && atoi(e) > 0) w = atoi(e);
     return w;
