@@ -208,6 +208,18 @@ def redistribute(idx, W, m1, m2, d, fraction, seed, epoch):
     return int(n), flags
 
 
+def redistribute_rows(idx, W, m1, m2, d, per_row, seed, epoch):
+    """In-place per-row prune (the per_row smallest |W| of every row) + random regrow.  Returns flags[m,k]."""
+    _chk(idx, np.int32), _chk(W), _chk(m1, np.float32), _chk(m2, np.float32)
+    m, k = idx.shape
+    assert 0 <= per_row <= k
+    flags = np.zeros((m, k), np.uint8)
+    lib().orc_redistribute_rows(_p(idx), _p(W), _p(m1), _p(m2), ctypes.c_int64(m), ctypes.c_int32(d),
+                                ctypes.c_int32(k), ctypes.c_int32(per_row), ctypes.c_uint64(seed),
+                                ctypes.c_uint64(epoch), ctypes.c_int(_storage(W)), _p(flags))
+    return flags
+
+
 def count_bad_rows(idx, d):
     _chk(idx, np.int32)
     m, k = idx.shape

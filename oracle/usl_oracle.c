@@ -328,6 +328,45 @@ int64_t orc_redistribute(int32_t* idx, void* W, float* m1, float* m2, int64_t m,
     return n;
 }
 
+/* The per-row variant of the redistribution (Section 2 leaves open whether the prune fraction is
+ * taken over the layer or over each unit; Section 3.2 only requires a constant count per label):
+ * every row loses its per_row connections of smallest magnitude, order (|W| bit pattern, slot t),
+ * and refills those slots exactly as orc_redistribute does.  pruned_flags as there. */
+void orc_redistribute_rows(int32_t* idx, void* W, float* m1, float* m2, int64_t m, int32_t d, int32_t k,
+                           int32_t per_row, uint64_t seed, uint64_t epoch, int storage,
+                           uint8_t* pruned_flags) {
+    if (per_row > k) per_row = k;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < m; ++j) {
+        uint64_t* keys = (uint64_t*)malloc((size_t)k * sizeof(uint64_t));
+        uint8_t* empty = (uint8_t*)calloc((size_t)k, 1);
+        for (int32_t t = 0; t < k; ++t) {
+            uint64_t mag;
+            if (storage == 0) {
+                uint32_t u;
+                memcpy(&u, (const float*)W + j * k + t, 4);
+                mag = u & 0x7FFFFFFFu;
+            } else {
+                mag = ((const uint16_t*)W)[j * k + t] & 0x7FFFu;
+            }
+            keys[t] = (mag << 32) | (uint64_t)t;
+        }
+        qsort(keys, (size_t)k, sizeof(uint64_t), cmp_u64);
+        for (int32_t r = 0; r < per_row; ++r) empty[keys[r] & 0xFFFFFFFFull] = 1;
+        for (int32_t t = 0; t < k; ++t) {
+            if (pruned_flags) pruned_flags[j * k + t] = empty[t];
+            if (!empty[t]) continue;
+            if (storage == 0) ((float*)W)[j * k + t] = 0.0f;
+            else ((uint16_t*)W)[j * k + t] = 0;
+            m1[j * k + t] = 0.0f;
+            m2[j * k + t] = 0.0f;
+        }
+        if (per_row > 0) regrow_row(idx + j * k, empty, j, d, k, seed, epoch);
+        free(keys);
+        free(empty);
+    }
+}
+
 /* Count rows that break the uniform-sparsity invariant: an index outside [0, d) or a
  * column that appears twice in one row. */
 int64_t orc_count_bad_rows(const int32_t* idx, int64_t m, int32_t d, int32_t k) {

@@ -469,3 +469,54 @@ def test_label_subset_products_are_slices_of_the_full_products(orc):
     dense = scatter_dense(idx, W, cfg.d)                                     # [m][d]
     ref = x.astype(np.float64) @ dense[rows].T
     assert_close(orc.forward_rows(x, idx, W, rows), ref, 1e-6, "subset scores vs dense")
+
+
+# ---------------------------------------------------------------- per-row variant of the redistribution
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+@pytest.mark.parametrize("m,d,k,per_row", [(300, 64, 8, 1), (200, 40, 32, 10), (64, 9, 8, 8), (33, 70, 5, 2)])
+def test_redistribute_rows_against_brute_force(orc, m, d, k, per_row, storage):
+    cfg = wl.custom(m, d, k, 1, storage=storage, index=81)
+    idx0, W0 = wl.gen_idx(cfg), wl.gen_W(cfg)
+    Wf = wl.as_f32(W0).copy()
+    Wf[3, :] = np.float32(0.5) * np.where(np.arange(k) % 2, 1, -1)      # a row of equal magnitudes: slots 0.. go
+    Wf[4, 0], Wf[4, 1] = 0.0, -0.0                                      # signed zeros tie, slot order decides
+    Wf[5, 2] = np.float32("nan")                                        # largest key: goes last
+    W0 = wl.store(Wf, storage)
+    m1_0 = np.full((m, k), 0.25, np.float32)
+    m2_0 = np.full((m, k), 0.5, np.float32)
+    idx, W, m1, m2 = idx0.copy(), W0.copy(), m1_0.copy(), m2_0.copy()
+    seed, epoch = 123, 9
+    flags = orc.redistribute_rows(idx, W, m1, m2, d, per_row, seed, epoch)
+    # second implementation of the prune rule: numpy lexsort per row
+    mag = (W0 & 0x7FFF).astype(np.int64) if W0.dtype == np.uint16 else (W0.view(np.uint32) & 0x7FFFFFFF).astype(np.int64)
+    ref = np.zeros((m, k), np.uint8)
+    for j in range(m):
+        order = np.lexsort((np.arange(k), mag[j]))
+        ref[j, order[:per_row]] = 1
+    np.testing.assert_array_equal(flags, ref)
+    assert (flags.sum(axis=1) == per_row).all()
+    assert flags[3, :per_row].all() and (per_row == k or not flags[5, 2])
+    keep = flags == 0
+    for new, old in ((idx, idx0), (W, W0), (m1, m1_0), (m2, m2_0)):
+        np.testing.assert_array_equal(new[keep].view(np.uint8), old[keep].view(np.uint8))
+    assert (W[flags == 1].view(np.uint8) == 0).all()
+    assert (m1[flags == 1] == 0).all() and (m2[flags == 1] == 0).all()
+    assert orc.count_bad_rows(idx, d) == 0
+    for j in range(m):                                      # refill rule, second implementation
+        assert idx[j].tolist() == py_regrow(idx0[j].tolist(), flags[j].astype(bool).tolist(), j, d, seed, epoch)
+
+
+def test_redistribute_rows_zero_and_all(orc):
+    cfg = wl.custom(50, 30, 8, 1)
+    idx0, W0 = wl.gen_idx(cfg), wl.gen_W(cfg)
+    idx, W = idx0.copy(), W0.copy()
+    m1, m2 = np.ones((50, 8), np.float32), np.ones((50, 8), np.float32)
+    assert orc.redistribute_rows(idx, W, m1, m2, 30, 0, 1, 0).sum() == 0
+    np.testing.assert_array_equal(idx, idx0); np.testing.assert_array_equal(W, W0)
+    assert orc.redistribute_rows(idx, W, m1, m2, 30, 8, 7, 3).all()
+    # every slot empty: the same as the initial connectivity rule under that (seed, epoch)
+    ref = idx0.copy()
+    for j in range(50):
+        ref[j] = py_regrow(idx0[j].tolist(), [True] * 8, j, 30, 7, 3)
+    np.testing.assert_array_equal(idx, ref)
