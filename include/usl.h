@@ -184,6 +184,13 @@ usl_status usl_redistribute(usl_ctx* ctx, int32_t* idx, void* W, float* m1, floa
                             double fraction, uint64_t seed, uint64_t epoch,
                             int64_t* n_rewired_host);
 
+/* The per-row variant of usl_redistribute (Section 2 does not say whether the prune fraction is taken
+ * over the layer or over each unit; this is the second reading): every row loses its per_row
+ * connections of smallest magnitude, order (bit pattern of |W|, slot t) -- so NaN goes last -- and the
+ * emptied slots are refilled by steps 2 and 3 of usl_redistribute.  0 <= per_row <= k. */
+usl_status usl_redistribute_rows(usl_ctx* ctx, int32_t* idx, void* W, float* m1, float* m2,
+                                 int32_t per_row, uint64_t seed, uint64_t epoch);
+
 /* Debug check of the uniform-sparsity invariant (Section 3.2): counts rows of idx that hold a
  * value outside [0, d) or the same column twice.  n_bad_host: host pointer; the call waits. */
 usl_status usl_validate_indices(usl_ctx* ctx, const int32_t* idx, int64_t* n_bad_host);

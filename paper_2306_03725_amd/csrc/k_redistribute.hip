@@ -176,6 +176,54 @@ k_mark(TS* __restrict__ W, float* __restrict__ m1, float* __restrict__ m2, size_
     }
 }
 
+// Per-row variant of the prune: GS lanes own one row (as in k_regrow); lane t ranks its own magnitude among the
+// row's by (key, slot) with GS shuffles and gives up its slot if fewer than per_row rank below it.
+template <int GS, typename TS>
+__global__ void __launch_bounds__(256)
+k_mark_rows(TS* __restrict__ W, float* __restrict__ m1, float* __restrict__ m2, int64_t m, int k, int per_row,
+            uint8_t* __restrict__ flags) {
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = gid / GS;
+    const int t = (int)(gid % GS);
+    const int lane = threadIdx.x & 63;
+    const int gbase = lane & ~(GS - 1);
+    const bool active = row < m && t < k;
+    const size_t f = (size_t)row * k + t;
+    const uint32_t key = active ? mag_key<TS>(W, f) : 0xFFFFFFFFu;   // idle lanes rank last
+    int rank = 0;
+#pragma unroll
+    for (int u = 0; u < GS; ++u) {
+        const uint32_t other = (uint32_t)__shfl((int)key, gbase + u);
+        rank += (other < key || (other == key && u < t)) ? 1 : 0;
+    }
+    if (active) {
+        const bool gone = rank < per_row;
+        flags[f] = gone ? 1 : 0;
+        if (gone) { W[f] = (TS)0; m1[f] = 0.f; m2[f] = 0.f; }
+    }
+}
+
+// any k: one thread per row; the flags of the whole row are settled before the first value is reset
+template <typename TS>
+__global__ void __launch_bounds__(256)
+k_mark_rows_serial(TS* __restrict__ W, float* __restrict__ m1, float* __restrict__ m2, int64_t m, int k,
+                   int per_row, uint8_t* __restrict__ flags) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= m) return;
+    const size_t f0 = (size_t)row * k;
+    for (int t = 0; t < k; ++t) {
+        const uint32_t key = mag_key<TS>(W, f0 + t);
+        int rank = 0;
+        for (int u = 0; u < k; ++u) {
+            const uint32_t other = mag_key<TS>(W, f0 + u);
+            rank += (other < key || (other == key && u < t)) ? 1 : 0;
+        }
+        flags[f0 + t] = rank < per_row ? 1 : 0;
+    }
+    for (int t = 0; t < k; ++t)
+        if (flags[f0 + t]) { W[f0 + t] = (TS)0; m1[f0 + t] = 0.f; m2[f0 + t] = 0.f; }
+}
+
 // ---- regrow ---------------------------------------------------------------------------------
 // GS lanes own one row (GS = power of two >= k, <= 64); lane t of the group holds slot t.
 // flags == nullptr means every slot is empty (initial connectivity).
@@ -332,6 +380,36 @@ usl_status redistribute_t(usl_ctx* c, int32_t* idx, TS* W, float* m1, float* m2,
     return regrow(c, idx, c->prune_flags, false, seed, epoch);
 }
 
+template <typename TS>
+usl_status redistribute_rows_t(usl_ctx* c, int32_t* idx, TS* W, float* m1, float* m2, int per_row,
+                               uint64_t seed, uint64_t epoch) {
+    USL_TRY(ensure_flags(c));
+    const int k = c->k;
+    if (k > 64) {
+        hipLaunchKernelGGL(k_mark_rows_serial<TS>, dim3((unsigned)((c->m + 255) / 256)), dim3(256), 0, c->stream,
+                           W, m1, m2, c->m, k, per_row, c->prune_flags);
+    } else {
+        int gs = 1;
+        while (gs < k) gs <<= 1;
+        const unsigned grid = (unsigned)((c->m * gs + 255) / 256);
+#define USL_MR(GS)                                                                                       \
+    hipLaunchKernelGGL((k_mark_rows<GS, TS>), dim3(grid), dim3(256), 0, c->stream, W, m1, m2, c->m, k,   \
+                       per_row, c->prune_flags)
+        switch (gs) {
+            case 1: USL_MR(1); break;
+            case 2: USL_MR(2); break;
+            case 4: USL_MR(4); break;
+            case 8: USL_MR(8); break;
+            case 16: USL_MR(16); break;
+            case 32: USL_MR(32); break;
+            default: USL_MR(64); break;
+        }
+#undef USL_MR
+    }
+    USL_TRY(usl_check_launch(c, "prune (per row)"));
+    return regrow(c, idx, c->prune_flags, false, seed, epoch);
+}
+
 }  // namespace
 
 usl_status usl_launch_redistribute(usl_ctx* c, int32_t* idx, void* W, float* m1, float* m2,
@@ -339,6 +417,13 @@ usl_status usl_launch_redistribute(usl_ctx* c, int32_t* idx, void* W, float* m1,
     return c->storage == USL_F32
                ? redistribute_t<float>(c, idx, (float*)W, m1, m2, n, seed, epoch)
                : redistribute_t<uint16_t>(c, idx, (uint16_t*)W, m1, m2, n, seed, epoch);
+}
+
+usl_status usl_launch_redistribute_rows(usl_ctx* c, int32_t* idx, void* W, float* m1, float* m2,
+                                        int32_t per_row, uint64_t seed, uint64_t epoch) {
+    return c->storage == USL_F32
+               ? redistribute_rows_t<float>(c, idx, (float*)W, m1, m2, per_row, seed, epoch)
+               : redistribute_rows_t<uint16_t>(c, idx, (uint16_t*)W, m1, m2, per_row, seed, epoch);
 }
 
 usl_status usl_launch_init_indices(usl_ctx* c, int32_t* idx, uint64_t seed) {

@@ -326,6 +326,19 @@ extern "C" usl_status usl_redistribute(usl_ctx* c, int32_t* idx, void* W, float*
     return usl_launch_redistribute(c, idx, W, m1, m2, n, seed, epoch);
 }
 
+extern "C" usl_status usl_redistribute_rows(usl_ctx* c, int32_t* idx, void* W, float* m1, float* m2,
+                                            int32_t per_row, uint64_t seed, uint64_t epoch) {
+    if (!c) return USL_EINVAL;
+    NEED(idx); NEED(W); NEED(m1); NEED(m2);
+    if (per_row < 0 || per_row > c->k) USL_FAIL(c, USL_EINVAL, "per_row %d outside [0, k]", per_row);
+    if (epoch == ~(uint64_t)0) USL_FAIL(c, USL_EINVAL, "epoch 2^64-1 is reserved for usl_init_indices");
+    if (per_row == 0) return USL_OK;
+    USL_TRY(usl_prepare_device(c));
+    c->csc_built_for = nullptr;
+    c->slot_order_for = nullptr;
+    return usl_launch_redistribute_rows(c, idx, W, m1, m2, per_row, seed, epoch);
+}
+
 extern "C" usl_status usl_validate_indices(usl_ctx* c, const int32_t* idx, int64_t* n_bad_host) {
     if (!c) return USL_EINVAL;
     NEED(idx); NEED(n_bad_host);

@@ -99,6 +99,8 @@ usl_status usl_launch_adam(usl_ctx* ctx, void* W, const float* grad_W, float* m1
                            float inv_c2);
 usl_status usl_launch_redistribute(usl_ctx* ctx, int32_t* idx, void* W, float* m1, float* m2,
                                    int64_t n, uint64_t seed, uint64_t epoch);
+usl_status usl_launch_redistribute_rows(usl_ctx* ctx, int32_t* idx, void* W, float* m1, float* m2,
+                                        int32_t per_row, uint64_t seed, uint64_t epoch);
 usl_status usl_launch_init_indices(usl_ctx* ctx, int32_t* idx, uint64_t seed);
 usl_status usl_launch_topk(usl_ctx* ctx, const float* out, int32_t b, int32_t kk, int32_t* top_lab,
                            float* top_val);

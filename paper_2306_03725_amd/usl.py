@@ -17,7 +17,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 # every symbol include/usl.h declares
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
-           "usl_topk", "usl_precision_hits", "usl_train_step",
+           "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
@@ -50,6 +50,7 @@ _sig = {
     "usl_backward_input": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32],
     "usl_redistribute": [_vp, _vp, _vp, _vp, _vp, _f64, _u64, _u64, ctypes.POINTER(_i64)],
+    "usl_redistribute_rows": [_vp, _vp, _vp, _vp, _vp, _i32, _u64, _u64],
     "usl_validate_indices": [_vp, _vp, ctypes.POINTER(_i64)],
     "usl_philox_words": [_vp, _vp, _u32, _u32, _vp, _i64],
 }
@@ -167,6 +168,9 @@ class Layer:
         self._ck(_lib.usl_redistribute(self._h, _ptr(idx), _ptr(W), _ptr(m1), _ptr(m2), fraction,
                                        seed, epoch, ctypes.byref(n)))
         return n.value
+
+    def redistribute_rows(self, idx, W, m1, m2, per_row, seed, epoch):
+        self._ck(_lib.usl_redistribute_rows(self._h, _ptr(idx), _ptr(W), _ptr(m1), _ptr(m2), per_row, seed, epoch))
 
     def validate_indices(self, idx):
         n = _i64(-1)

@@ -294,6 +294,42 @@ def test_redistribute_bit_exact(usl, gu, orc, name, storage, frac):
     assert_close(got[fin], ref[fin], 1e-4, "grad_x after redistribution")
 
 
+REDIST_ROWS = [("tiny", "f32", 1), ("tiny", "bf16", 3), ("ragged_small", "f32", 2), ("ragged_small", "bf16", 32),
+               ("k5", "f32", 2), ("k33", "f32", 16), ("k_eq_d", "f32", 9), ("k64", "bf16", 5),
+               ("big_blocks", "f32", 3), ("one", "f32", 1), ("tiny", "f32", 0)]
+
+
+@pytest.mark.parametrize("name,storage,per_row", REDIST_ROWS)
+def test_redistribute_rows_bit_exact(usl, gu, orc, name, storage, per_row):
+    """The per-row variant: every row loses its per_row smallest connections."""
+    cfg = make(name, storage)
+    m, d, k = cfg.m, cfg.d, cfg.k
+    idx, W = wl.gen_idx(cfg), wl.gen_W(cfg)
+    Wf = wl.as_f32(W).copy()
+    if m > 10:      # a row of equal magnitudes, signed zeros, a NaN
+        Wf[3, :] = np.float32(0.5) * np.where(np.arange(k) % 2, 1, -1)
+        Wf[4, 0] = 0.0
+        Wf[4, k - 1] = -0.0
+        Wf[5, k // 2] = np.float32("nan")
+    W = wl.store(Wf, storage)
+    r = wl.rng(cfg, 9)
+    m1 = r.standard_normal((m, k)).astype(np.float32)
+    m2 = r.random((m, k)).astype(np.float32)
+    seed, epoch = wl.redistribution_seed(cfg), 5
+    L = usl.Layer(m, d, k, cfg.b, storage)
+    d_idx, d_W, d_m1, d_m2 = gu.dev(idx), gu.dev(W), gu.dev(m1), gu.dev(m2)
+    L.redistribute_rows(d_idx, d_W, d_m1, d_m2, per_row, seed, epoch)
+    flags = orc.redistribute_rows(idx, W, m1, m2, d, per_row, seed, epoch)     # in place on the host copies
+    assert int(flags.sum()) == per_row * m
+    np.testing.assert_array_equal(gu.host(d_idx), idx)
+    np.testing.assert_array_equal(gu.host(d_W).view(np.uint8), W.view(np.uint8))
+    np.testing.assert_array_equal(gu.host(d_m1).view(np.uint8), m1.view(np.uint8))
+    np.testing.assert_array_equal(gu.host(d_m2).view(np.uint8), m2.view(np.uint8))
+    assert L.validate_indices(d_idx) == 0
+    with pytest.raises(usl.UslError):
+        L.redistribute_rows(d_idx, d_W, d_m1, d_m2, k + 1, seed, epoch)
+
+
 def run_schedule(usl, gu, orc, cfg, steps):
     """Whole train loop on the GPU; before every call the oracle is handed the GPU's current state
     (teacher forcing), so each call is checked on identical inputs."""
