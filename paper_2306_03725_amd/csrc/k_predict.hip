@@ -44,34 +44,56 @@ __device__ __forceinline__ uint64_t block_max(uint64_t v, uint64_t* red) {
 //      every key >= tau belongs to one of the kk lanes whose maximum is >= tau, so at most kk*64 keys pass;
 //   3. those keys are collected in LDS and the best kk are peeled off one by one ("largest key below the
 //      previous winner": keys are distinct, so nothing has to be removed).
+// VEC: rows are 16-byte aligned and m % 4 == 0, so a lane reads 16 groups of 4 consecutive labels.
+template <bool VEC>
 __global__ void __launch_bounds__(TK_NT)
 k_topk_segments(const float* __restrict__ out, int64_t m, int kk, int nseg, uint64_t* __restrict__ cand) {
     __shared__ uint64_t red[TK_NT / 64];
     __shared__ uint64_t list[TK_MAX * TK_EPT];
     __shared__ uint32_t count;
-    const int64_t j0 = (int64_t)blockIdx.x * TK_SEG + threadIdx.x;
+    const int64_t seg0 = (int64_t)blockIdx.x * TK_SEG;
     const float* row = out + (int64_t)blockIdx.y * m;
+    // label of register e of this lane
+    auto label_of = [&](int e) -> int64_t {
+        return VEC ? seg0 + ((int64_t)(e >> 2) * TK_NT + threadIdx.x) * 4 + (e & 3)
+                   : seg0 + (int64_t)e * TK_NT + threadIdx.x;
+    };
     float v[TK_EPT];
+    if (VEC) {
+#pragma unroll
+        for (int e = 0; e < TK_EPT; e += 4) {
+            const int64_t j = label_of(e);
+            const float4 q = j < m ? *reinterpret_cast<const float4*>(row + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v[e] = q.x; v[e + 1] = q.y; v[e + 2] = q.z; v[e + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < TK_EPT; ++e) {
+            const int64_t j = label_of(e);
+            v[e] = j < m ? row[j] : 0.f;
+        }
+    }
+    // the lane's best score; labels grow with e, so the first of equal scores is the smaller label
+    float top = 0.f;
+    int top_e = -1;
 #pragma unroll
     for (int e = 0; e < TK_EPT; ++e) {
-        const int64_t j = j0 + (int64_t)e * TK_NT;
-        v[e] = j < m ? row[j] : 0.f;
+        const bool better = label_of(e) < m && (top_e < 0 || v[e] > top);
+        top = better ? v[e] : top;
+        top_e = better ? e : top_e;
     }
-    uint64_t mine = 0;
-#pragma unroll
-    for (int e = 0; e < TK_EPT; ++e) {
-        const int64_t j = j0 + (int64_t)e * TK_NT;
-        const uint64_t key = j < m ? score_key(v[e], (uint32_t)j) : 0ull;
-        mine = key > mine ? key : mine;
-    }
+    const uint64_t mine = top_e >= 0 ? score_key(top, (uint32_t)label_of(top_e)) : 0ull;
     uint64_t tau = ~0ull;
     for (int r = 0; r < kk && tau != 0; ++r) tau = block_max(mine < tau ? mine : 0ull, red);
     if (threadIdx.x == 0) count = 0;
     __syncthreads();
+    // keys are built only for scores that reach tau's score (a cheap float test first)
+    const uint32_t tu = (uint32_t)(tau >> 32);
+    const float tau_score = tau == 0 ? -INFINITY : __uint_as_float((tu & 0x80000000u) ? (tu & 0x7FFFFFFFu) : ~tu);
 #pragma unroll
     for (int e = 0; e < TK_EPT; ++e) {
-        const int64_t j = j0 + (int64_t)e * TK_NT;
-        if (j < m) {
+        const int64_t j = label_of(e);
+        if (j < m && v[e] >= tau_score) {
             const uint64_t key = score_key(v[e], (uint32_t)j);
             if (key >= tau) list[atomicAdd(&count, 1u)] = key;
         }
@@ -139,8 +161,12 @@ usl_status usl_launch_topk(usl_ctx* c, const float* out, int32_t b, int32_t kk, 
                            float* top_val) {
     const int nseg = (int)((c->m + TK_SEG - 1) / TK_SEG);
     USL_TRY(usl_reserve(c, (void**)&c->topk_cand, &c->topk_cand_cap, (size_t)b * nseg * kk * 8));
-    hipLaunchKernelGGL(k_topk_segments, dim3((unsigned)nseg, (unsigned)b), dim3(TK_NT), 0, c->stream, out,
-                       c->m, (int)kk, nseg, c->topk_cand);
+    if (c->m % 4 == 0 && (uintptr_t)out % 16 == 0)
+        hipLaunchKernelGGL(k_topk_segments<true>, dim3((unsigned)nseg, (unsigned)b), dim3(TK_NT), 0, c->stream, out,
+                           c->m, (int)kk, nseg, c->topk_cand);
+    else
+        hipLaunchKernelGGL(k_topk_segments<false>, dim3((unsigned)nseg, (unsigned)b), dim3(TK_NT), 0, c->stream, out,
+                           c->m, (int)kk, nseg, c->topk_cand);
     hipLaunchKernelGGL(k_topk_merge, dim3((unsigned)b), dim3(TK_NT), 0, c->stream, c->topk_cand, nseg * kk,
                        (int)kk, out, c->m, top_lab, top_val);
     return usl_check_launch(c, "topk");

@@ -33,6 +33,14 @@ def test_train_step(orc, m, d, k, b, storage, loss_kind, with_gx, easy):
     if easy:      # all weights negative and large on non-negative activations: scores far below -1
         W = wl.store(-np.abs(wl.as_f32(W)) * 8.0 - 0.5, storage)
     off, lab = wl.gen_targets(cfg)
+    if m == 3001 or m == 3000:   # an instance without positives, repeated ids, a very dense instance
+        lists = [list(lab[off[i]:off[i + 1]]) for i in range(b)]
+        lists[0] = []
+        lists[1] = lists[1] + lists[1][:2]
+        lists[2] = list(range(0, m, 3))
+        lists[b - 1] = [m - 1, 0]
+        off = np.cumsum([0] + [len(l) for l in lists]).astype(np.int64)
+        lab = np.array([v for l in lists for v in l], np.int32)
     r = wl.rng(cfg, 5)
     m1 = (r.standard_normal((m, k)) * 1e-3).astype(np.float32)
     m2 = (r.random((m, k)) * 1e-6).astype(np.float32)
