@@ -295,46 +295,41 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
         }
     }
     // Lists are short (window labels * k / d entries: 24 at Large), so the walk is a chain of
-    // dependent load latencies, not a stream.  U entries go per trip, the tail is masked rather than
-    // walked one by one, and the next trip's (label, weight) pairs are requested while this trip's
-    // pieces are in flight.  The 8 lanes of a group read the same entry.
+    // dependent load latencies, not a stream, and the memory pipeline spends as long on a one-word
+    // load as on a 16-byte one.  U entries go per trip: lane s of the group fetches the (label, weight)
+    // of entry s with one load each and the group passes them round by lane shuffles; the tail is
+    // masked rather than walked one by one; the next trip's pairs are requested while this trip's
+    // pieces are in flight.
     constexpr int U = 8;
     if (p < p1) {
-        int32_t j[U];
-        float w[U];
-#pragma unroll
-        for (int q = 0; q < U; ++q) {
-            const uint32_t pp = min(p + q, p1 - 1);
-            j[q] = label[pp];
-            w[q] = wl[pp];
-        }
+        const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
+        uint32_t pp = min(p + sub, p1 - 1);
+        int32_t jm = label[pp];
+        float wm = p + sub < p1 ? wl[pp] : 0.f;   // a masked entry adds 0*0, whatever the repeated piece holds
         while (true) {
+            int32_t j[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) j[q] = __shfl(jm, gl + q);
             float4 v[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
-            const uint32_t pn = p + U;
-            int32_t jn[U];
-            float wn[U];
-            if (pn < p1) {
+            float w[U];
 #pragma unroll
-                for (int q = 0; q < U; ++q) {
-                    const uint32_t pp = min(pn + q, p1 - 1);
-                    jn[q] = label[pp];
-                    wn[q] = wl[pp];
-                }
+            for (int q = 0; q < U; ++q) w[q] = __shfl(wm, gl + q);
+            const uint32_t pn = p + U;
+            if (pn < p1) {
+                pp = min(pn + sub, p1 - 1);
+                jm = label[pp];
+                wm = pn + sub < p1 ? wl[pp] : 0.f;
             }
 #pragma unroll
             for (int q = 0; q < U; ++q) {
-                const bool live = p + q < p1;   // a masked entry adds 0*0, whatever the repeated piece holds
-                const float ww = live ? w[q] : 0.f;
-                const float4 vv = live ? v[q] : make_float4(0.f, 0.f, 0.f, 0.f);
-                acc.x = fmaf(ww, vv.x, acc.x); acc.y = fmaf(ww, vv.y, acc.y);
-                acc.z = fmaf(ww, vv.z, acc.z); acc.w = fmaf(ww, vv.w, acc.w);
+                const float4 vv = p + q < p1 ? v[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+                acc.x = fmaf(w[q], vv.x, acc.x); acc.y = fmaf(w[q], vv.y, acc.y);
+                acc.z = fmaf(w[q], vv.z, acc.z); acc.w = fmaf(w[q], vv.w, acc.w);
             }
             if (pn >= p1) break;
             p = pn;
-#pragma unroll
-            for (int q = 0; q < U; ++q) { j[q] = jn[q]; w[q] = wn[q]; }
         }
     }
     float4* dst = reinterpret_cast<float4*>(gxT + ((size_t)blockIdx.x * d + c) * 32 + (threadIdx.x & 7) * 4);
