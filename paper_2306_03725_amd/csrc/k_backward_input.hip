@@ -136,8 +136,8 @@ k_scan_apply(uint32_t* __restrict__ cursor /* in: counts */, const uint32_t* __r
 // The order of a list's entries is therefore not fixed; the sums that walk it do not fix theirs either.
 __global__ void __launch_bounds__(CSC_NT)
 k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_labels, int splits,
-           const uint32_t* __restrict__ ptr, uint32_t* __restrict__ taken,
-           uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
+           const uint32_t* __restrict__ ptr /* by rank */, const uint32_t* __restrict__ rank_of,
+           uint32_t* __restrict__ taken, uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
     extern __shared__ uint32_t cur[];
     const int c0 = blockIdx.y * CSC_CHUNK, nc = min(CSC_CHUNK, d - c0);
     size_t e0, e1;
@@ -146,7 +146,7 @@ k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_lab
     const size_t bin0 = (size_t)(blockIdx.x / splits) * d + c0;
     for (int q = threadIdx.x; q < nc; q += CSC_NT) {
         const uint32_t n = cur[q];
-        if (n) cur[q] = ptr[bin0 + q] + atomicAdd(&taken[bin0 + q], n);
+        if (n) cur[q] = ptr[bin0 - c0 + rank_of[bin0 + q]] + atomicAdd(&taken[bin0 + q], n);
     }
     __syncthreads();
     for (size_t e = e0 + threadIdx.x; e < e1; e += CSC_NT) {
@@ -156,6 +156,34 @@ k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_lab
             slot[pos] = (uint32_t)e;
             label[pos] = (int32_t)(e / (size_t)k);
         }
+    }
+}
+
+// Features of one window in the order of falling list length (one workgroup per window).  A wavefront
+// of the gather kernel walks 8 lists in lockstep and pays for the longest of them; with this order the 8
+// are of (nearly) one length.  The lists themselves are laid out in this order too, so neighbours in the
+// kernel are neighbours in memory.  order[rank] = feature, rank_of[feature] = rank, by_rank[rank] = its
+// list length.  Lists of 1023 entries or more share the first bucket.
+__global__ void __launch_bounds__(1024)
+k_csc_order(const uint32_t* __restrict__ count, int d, uint32_t* __restrict__ order,
+            uint32_t* __restrict__ rank_of, uint32_t* __restrict__ by_rank) {
+    __shared__ uint32_t start[1024];
+    const size_t w0 = (size_t)blockIdx.x * d;
+    start[threadIdx.x] = 0;
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += 1024) atomicAdd(&start[min(count[w0 + c], 1023u)], 1u);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int q = 1023; q >= 0; --q) { const uint32_t n = start[q]; start[q] = run; run += n; }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < d; c += 1024) {
+        const uint32_t n = count[w0 + c];
+        const uint32_t r = atomicAdd(&start[min(n, 1023u)], 1u);
+        order[w0 + r] = (uint32_t)c;
+        rank_of[w0 + c] = r;
+        by_rank[w0 + r] = n;
     }
 }
 
@@ -253,14 +281,16 @@ k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, in
 // list of one feature, lane l of the group owns instances 4l..4l+3 of the tile.
 __global__ void __launch_bounds__(256)
 k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
-                   const uint32_t* __restrict__ ptr /* this window's d+1 offsets */,
+                   const uint32_t* __restrict__ ptr /* this window's d+1 offsets, by rank */,
+                   const uint32_t* __restrict__ order /* this window's features by falling list length */,
                    const int32_t* __restrict__ label, float* __restrict__ gxT, int d,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
                    int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
-    const int c = blockIdx.y * 32 + (threadIdx.x >> 3);
-    if (c >= d) return;
-    uint32_t p = ptr[c];
-    const uint32_t p1 = ptr[c + 1];
+    const int rank = blockIdx.y * 32 + (threadIdx.x >> 3);
+    if (rank >= d) return;
+    const int c = (int)order[rank];
+    uint32_t p = ptr[rank];
+    const uint32_t p1 = ptr[rank + 1];
     const float* col = gT + (size_t)blockIdx.x * m * 32 + (threadIdx.x & 7) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     // Mostly-zero gradient (decided on the device from the cell count, the same for every lane):
@@ -386,15 +416,20 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
         USL_TRY(usl_reserve(c, (void**)&c->tie_counts, &cap, nchunks * 4));
         c->tie_counts_cap = cap;
     }
-    hipLaunchKernelGGL(k_scan_sums, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, c->csc_cursor,
+    USL_TRY(usl_reserve(c, (void**)&c->csc_order, &c->csc_order_cap, 3 * nbins * 4));
+    uint32_t* rank_of = c->csc_order + nbins;
+    uint32_t* by_rank = c->csc_order + 2 * nbins;
+    hipLaunchKernelGGL(k_csc_order, dim3((unsigned)nwin), dim3(1024), 0, c->stream, c->csc_cursor, c->d,
+                       c->csc_order, rank_of, by_rank);
+    hipLaunchKernelGGL(k_scan_sums, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, by_rank,
                        nbins, c->tie_counts);
     hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(SCAN_NT), 0, c->stream, c->tie_counts, nchunks,
                        c->csc_ptr + nbins);
-    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, c->csc_cursor,
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nchunks), dim3(SCAN_NT), 0, c->stream, by_rank,
                        c->tie_counts, nbins, c->csc_ptr);
     hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
     hipLaunchKernelGGL(k_csc_fill, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
-                       splits, c->csc_ptr, c->csc_cursor, c->csc_slot, c->csc_label);
+                       splits, c->csc_ptr, rank_of, c->csc_cursor, c->csc_slot, c->csc_label);
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
     return USL_OK;
@@ -439,7 +474,8 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
         for (int w = 0; w < nwin; ++w)
             hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                               c->csc_ptr + (size_t)w * c->d, c->csc_label, c->gxT, c->d,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_label,
+                               c->gxT, c->d,
                                w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
     }
     {

@@ -29,6 +29,7 @@ struct usl_ctx {
     // transposed (column-major) connectivity for backward_input
     uint32_t* csc_ptr;        size_t csc_ptr_cap;     // [nwin*d+1] start of each (window, feature) list
     uint32_t* csc_cursor;     size_t csc_cursor_cap;  // [nwin*d]
+    uint32_t* csc_order;      size_t csc_order_cap;   // [3][nwin*d] features of each window by falling list length; rank of each feature; list length by rank
     uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by (label window, feature)
     int32_t* csc_label;       // [m*k] label j of that slot
     float* csc_w;             // [m*k] W of that slot (refreshed by every backward_input)
