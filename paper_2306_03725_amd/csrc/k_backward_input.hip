@@ -297,27 +297,18 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
     // look the piece up in the flag table first and fetch only pieces that hold something.
     if (*nz_cells < sparse_below) {
         const uint8_t* fl = nzf + (size_t)blockIdx.x * m;
-        for (; p + 4 <= p1; p += 4) {
-            int32_t j[4];
-            uint8_t f[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) j[q] = label[p + q];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) f[q] = fl[j[q]];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (f[q]) {
-                    const float w = wl[p + q];
-                    const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
-                    acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
-                    acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
-                }
-            }
-        }
-        for (; p < p1; ++p) {
-            const int32_t j = label[p];
-            if (fl[j]) {
-                const float w = wl[p];
+        const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
+        for (; p < p1; p += 8) {   // lane s of the group looks entry s up; the group then visits the live ones
+            const uint32_t pp = min(p + sub, p1 - 1);
+            const int32_t jm = label[pp];
+            const float wm = wl[pp];
+            const bool live = p + sub < p1 && fl[jm] != 0;
+            uint32_t todo = (uint32_t)(__ballot(live) >> gl) & 0xFFu;
+            while (todo) {
+                const int q = __ffs(todo) - 1;
+                todo &= todo - 1;
+                const int32_t j = __shfl(jm, gl + q);
+                const float w = __shfl(wm, gl + q);
                 const float4 v = *reinterpret_cast<const float4*>(col + (size_t)j * 32);
                 acc.x = fmaf(w, v.x, acc.x); acc.y = fmaf(w, v.y, acc.y);
                 acc.z = fmaf(w, v.z, acc.z); acc.w = fmaf(w, v.w, acc.w);
