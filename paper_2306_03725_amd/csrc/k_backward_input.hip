@@ -5,17 +5,20 @@
 // LDS float atomics come near the needed rate (b*m*k additions), so the sum is turned into a gather
 // over a private column-major view of the connectivity, rebuilt whenever idx changes.
 //
-// Memory plan.  g is transposed to gT[m][b] so that the values of one label are contiguous.  The
-// naive gather (one wavefront per feature reading whole 1 KiB rows of gT) re-reads every row k
-// times from HBM / Infinity Cache (m*k*b*4 bytes: 16 GB at m=500k, k=32, b=256).  Instead:
-//   * the batch is cut into tiles of 32 instances (128-byte pieces of a gT row, one cache line),
-//     and the tile index is the fastest grid dimension, so that with round-robin dispatch of
-//     workgroups to the 8 XCDs all work on tile t lands on XCD t mod 8 and shares one L2;
+// Memory plan.  g is re-laid as gT[tile][m][32]: the batch is cut into tiles of 32 instances and every
+// (tile, label) owns one contiguous 128-byte piece (one cache line).  The naive gather (one wavefront per
+// feature reading all of a label's values) re-reads every label k times from HBM / Infinity Cache
+// (m*k*b*4 bytes: 16 GB at m=500k, k=32, b=256).  Instead:
+//   * the tile index is the fastest grid dimension, so that with round-robin dispatch of workgroups to
+//     the 8 XCDs all work on tile t lands on XCD t mod 8 and shares one L2;
 //   * the labels are cut into windows whose tile-slice of gT fits that L2; the kernel is launched
 //     once per window and handles the connections of every feature that fall into the window, so
 //     each 128-byte piece is fetched once and then served k times from L2;
-//   * the column lists are therefore grouped by (window, feature); partial sums are added into
-//     gxT[d][b] by the later windows (plain read-modify-write: launches are ordered).
+//   * the column lists are therefore grouped by (window, feature), and inside a window ordered by
+//     falling length; partial sums are added into gxT[tile][d][32] by the later windows (plain
+//     read-modify-write: launches are ordered).
+// A list entry is the flat slot number j*k+t of a connection: the label is slot / k, and the same
+// number tells the per-call weight gather where W[j][t] lives.
 // Eight lanes (8 x float4 = 32 instances) form a group that walks one feature's list; a wavefront
 // reads eight 128-byte pieces per load instruction.  No atomics touch grad_x; the only
 // non-determinism is the order of the slots inside one (window, feature) list.
@@ -137,7 +140,7 @@ k_scan_apply(uint32_t* __restrict__ cursor /* in: counts */, const uint32_t* __r
 __global__ void __launch_bounds__(CSC_NT)
 k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_labels, int splits,
            const uint32_t* __restrict__ ptr /* by rank */, const uint32_t* __restrict__ rank_of,
-           uint32_t* __restrict__ taken, uint32_t* __restrict__ slot, int32_t* __restrict__ label) {
+           uint32_t* __restrict__ taken, uint32_t* __restrict__ slot) {
     extern __shared__ uint32_t cur[];
     const int c0 = blockIdx.y * CSC_CHUNK, nc = min(CSC_CHUNK, d - c0);
     size_t e0, e1;
@@ -154,7 +157,6 @@ k_csc_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int win_lab
         if (c < (uint32_t)nc) {
             const uint32_t pos = atomicAdd(&cur[c], 1u);
             slot[pos] = (uint32_t)e;
-            label[pos] = (int32_t)(e / (size_t)k);
         }
     }
 }
@@ -283,12 +285,14 @@ __global__ void __launch_bounds__(256)
 k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ ptr /* this window's d+1 offsets, by rank */,
                    const uint32_t* __restrict__ order /* this window's features by falling list length */,
-                   const int32_t* __restrict__ label, float* __restrict__ gxT, int d,
+                   const uint32_t* __restrict__ slot, int k, int kshift /* log2 k, or -1 */,
+                   float* __restrict__ gxT, int d,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
                    int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
     const int rank = blockIdx.y * 32 + (threadIdx.x >> 3);
     if (rank >= d) return;
     const int c = (int)order[rank];
+    auto label_of = [&](uint32_t e) -> int32_t { return (int32_t)(kshift >= 0 ? e >> kshift : e / (uint32_t)k); };
     uint32_t p = ptr[rank];
     const uint32_t p1 = ptr[rank + 1];
     const float* col = gT + (size_t)blockIdx.x * m * 32 + (threadIdx.x & 7) * 4;
@@ -300,7 +304,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
         const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
         for (; p < p1; p += 8) {   // lane s of the group looks entry s up; the group then visits the live ones
             const uint32_t pp = min(p + sub, p1 - 1);
-            const int32_t jm = label[pp];
+            const int32_t jm = label_of(slot[pp]);
             const float wm = wl[pp];
             const bool live = p + sub < p1 && fl[jm] != 0;
             uint32_t todo = (uint32_t)(__ballot(live) >> gl) & 0xFFu;
@@ -325,7 +329,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
     if (p < p1) {
         const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
         uint32_t pp = min(p + sub, p1 - 1);
-        int32_t jm = label[pp];
+        int32_t jm = label_of(slot[pp]);
         float wm = p + sub < p1 ? wl[pp] : 0.f;   // a masked entry adds 0*0, whatever the repeated piece holds
         while (true) {
             int32_t j[U];
@@ -340,7 +344,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             const uint32_t pn = p + U;
             if (pn < p1) {
                 pp = min(pn + sub, p1 - 1);
-                jm = label[pp];
+                jm = label_of(slot[pp]);
                 wm = pn + sub < p1 ? wl[pp] : 0.f;
             }
 #pragma unroll
@@ -384,7 +388,6 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
         c->csc_cursor_cap = cap;
         if (!c->csc_slot) {
             cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_slot, &cap, N * 4));
-            cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_label, &cap, N * 4));
             cap = 0; USL_TRY(usl_reserve(c, (void**)&c->csc_w, &cap, N * 4));
         }
         c->csc_win_labels = wl;
@@ -420,7 +423,7 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
                        c->tie_counts, nbins, c->csc_ptr);
     hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
     hipLaunchKernelGGL(k_csc_fill, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
-                       splits, c->csc_ptr, rank_of, c->csc_cursor, c->csc_slot, c->csc_label);
+                       splits, c->csc_ptr, rank_of, c->csc_cursor, c->csc_slot);
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
     return USL_OK;
@@ -449,6 +452,9 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
     const int ntile = (b + 31) / 32;
+    int kshift = -1;
+    for (int q = 0; q < 31; ++q)
+        if ((1 << q) == c->k) kshift = q;
     {   // weights in list order
         const unsigned blocks = (unsigned)((nwin + 7) / 8) * 8 * GW_BPW;
         if (c->storage == USL_F32)
@@ -465,8 +471,8 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
         for (int w = 0; w < nwin; ++w)
             hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_label,
-                               c->gxT, c->d,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                               c->k, kshift, c->gxT, c->d,
                                w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
     }
     {

@@ -31,7 +31,6 @@ struct usl_ctx {
     uint32_t* csc_cursor;     size_t csc_cursor_cap;  // [nwin*d]
     uint32_t* csc_order;      size_t csc_order_cap;   // [3][nwin*d] features of each window by falling list length; rank of each feature; list length by rank
     uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by (label window, feature)
-    int32_t* csc_label;       // [m*k] label j of that slot
     float* csc_w;             // [m*k] W of that slot (refreshed by every backward_input)
     int csc_win_labels;       // labels per window the lists were built with
     const int32_t* csc_built_for;  // idx pointer the lists were built from (NULL = stale)
