@@ -38,12 +38,14 @@ struct TileGeom {
     int inst_per_group; // instances handled by one blockIdx.y
     int vec_ok;         // 16-byte copies allowed
     int flag_offset;    // byte offset in LDS of the per-wavefront flags of backward_weight
+    int buf_stride;     // elements between the two row buffers of MODE 3 (0 = one buffer)
 };
 
 // ---------------------------------------------------------------------------- forward
 // MODE 0: a whole activation row fits LDS, one row per stage.
 // MODE 1: the row is cut into slices of part_cols columns; gathers outside the slice are masked.
 // MODE 2: small rows, rows_per_tile of them per stage (used with one label per lane).
+// MODE 3: two rows fit LDS: the next row is copied in while this one is gathered (one barrier per instance).
 template <int K, int LPT, int NT, typename TS, int MODE>
 __global__ void __launch_bounds__(NT)
 k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* __restrict__ W,
@@ -73,7 +75,45 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
   // label of slot l is jme + l*NT
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
-    if (MODE == 2) {
+    if (MODE == 3) {
+        float prev[LPT];
+        __syncthreads();   // the transposition buffer is free
+        if (i_begin < i_end) stage<TS, NT>(x + (size_t)i_begin * d, lds, d, tg.vec_ok);
+        __syncthreads();
+#pragma unroll 1
+        for (int i = i_begin; i < i_end; ++i) {
+            const TS* cur = lds + (size_t)((i - i_begin) & 1) * tg.buf_stride;
+            // the other buffer was last read one instance ago, before the barrier that ended it
+            if (i + 1 < i_end)
+                stage<TS, NT, false>(x + (size_t)(i + 1) * d, lds + (size_t)((i + 1 - i_begin) & 1) * tg.buf_stride, d,
+                                     tg.vec_ok);
+            if (i > i_begin) {
+#pragma unroll
+                for (int l = 0; l < LPT; ++l)
+                    if (jme + (int64_t)l * NT < m) out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
+            }
+            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d);
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) {
+                float acc = 0.f;
+                keep_packed(pk[l]);
+#pragma unroll
+                for (int t = 0; t < K; ++t) {
+                    acc = fmaf(w[l][t], lds_val(cur, col_of<K>(pk[l], t)), acc);
+                    if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                }
+                asm volatile("" : "+v"(acc));
+                prev[l] = acc;
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next row has landed
+            __syncthreads();
+        }
+        if (i_end > i_begin) {
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+                if (jme + (int64_t)l * NT < m) out[(size_t)(i_end - 1) * m + jme + (int64_t)l * NT] = prev[l];
+        }
+    } else if (MODE == 2) {
         for (int it = i_begin; it < i_end; it += tg.rows_per_tile) {
             const int rows = min(tg.rows_per_tile, i_end - it);
             __syncthreads();
@@ -206,7 +246,68 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
 
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
-    if (MODE == 2) {
+    if (MODE == 3) {
+        // as in the single-buffer loop below, an instance (a label group) whose gradients are all zero skips
+        // its gathers; the row copy is not skipped, it runs one instance ahead
+        uint32_t* live_flags = reinterpret_cast<uint32_t*>(lds_raw + tg.flag_offset);
+        float gnext[LPT];
+        bool any_next = false;
+#pragma unroll
+        for (int l = 0; l < LPT; ++l) {
+            const int64_t j = jme + (int64_t)l * NT;
+            gnext[l] = (j < m && i_begin < i_end) ? g[(size_t)i_begin * m + j] : 0.f;
+            any_next = any_next || gnext[l] != 0.f;
+        }
+        __syncthreads();   // the transposition buffer is free
+        if (i_begin < i_end) stage<TS, NT>(x + (size_t)i_begin * d, lds, d, tg.vec_ok);
+        {
+            const bool wave_any = __any(any_next);
+            if ((threadIdx.x & 63) == 0) live_flags[threadIdx.x >> 6] = wave_any ? 1u : 0u;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int i = i_begin; i < i_end; ++i) {
+            const TS* cur = lds + (size_t)((i - i_begin) & 1) * tg.buf_stride;
+            if (i + 1 < i_end)
+                stage<TS, NT, false>(x + (size_t)(i + 1) * d, lds + (size_t)((i + 1 - i_begin) & 1) * tg.buf_stride, d,
+                                     tg.vec_ok);
+            float gv[LPT];
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) gv[l] = gnext[l];
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) {
+                const int64_t j = jme + (int64_t)l * NT;
+                gnext[l] = (j < m && i + 1 < i_end) ? g[(size_t)(i + 1) * m + j] : 0.f;
+            }
+            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d);
+            const uint32_t* wf = live_flags + ((i - i_begin) & 1) * (NT / 64);
+            uint32_t live = 0;
+#pragma unroll
+            for (int q = 0; q < NT / 64; ++q) live |= wf[q];
+            if (live) {
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) {
+                    if (!__any(gv[l] != 0.f)) continue;
+                    keep_packed(pk[l]);
+#pragma unroll
+                    for (int t = 0; t < K; ++t) {
+                        acc[l][t] = fmaf(gv[l], lds_val(cur, col_of<K>(pk[l], t)), acc[l][t]);
+                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next row and the next gradients have landed
+            {
+                bool any = false;
+#pragma unroll
+                for (int l = 0; l < LPT; ++l) any = any || gnext[l] != 0.f;
+                const bool wave_any = __any(any);
+                if ((threadIdx.x & 63) == 0)
+                    live_flags[((i + 1 - i_begin) & 1) * (NT / 64) + (threadIdx.x >> 6)] = wave_any ? 1u : 0u;
+            }
+            __syncthreads();
+        }
+    } else if (MODE == 2) {
         for (int it = i_begin; it < i_end; it += tg.rows_per_tile) {
             const int rows = min(tg.rows_per_tile, i_end - it);
             __syncthreads();
@@ -374,6 +475,11 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     *lds_bytes = tg.nparts == 1 ? (size_t)tg.rows_per_tile * row_bytes
                                 : (size_t)tg.part_cols * esize + 128;   // + the zero words
     *lds_bytes = (*lds_bytes + 15) & ~(size_t)15;
+    tg.buf_stride = 0;
+    if (!multi_row && tg.nparts == 1 && 2 * *lds_bytes + 256 <= (size_t)USL_ROW_LDS_BYTES + 8192) {
+        tg.buf_stride = (int)(*lds_bytes / esize);   // a second row buffer: copy and gathers overlap
+        *lds_bytes *= 2;
+    }
     tg.flag_offset = (int)*lds_bytes;
     *lds_bytes += 256;                                                   // + per-wavefront flags
     return tg;
@@ -408,6 +514,7 @@ usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void
     } while (0)
     if (tg.nparts > 1) USL_FW(1);
     else if (LPT == 1 && tg.rows_per_tile > 1) USL_FW(LPT == 1 ? 2 : 0);
+    else if (tg.buf_stride) USL_FW(LPT == 1 ? 0 : 3);
     else USL_FW(0);
 #undef USL_FW
     return usl_check_launch(c, "forward");
@@ -449,8 +556,9 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
         hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT>), grid, dim3(NT), lds, \
                            c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);  \
     } while (0)
-    const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : 0);
+    const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : (tg.buf_stride && LPT > 1 ? 3 : 0));
     if (mode == 1) { if (G > 1) USL_BW(1, true); else USL_BW(1, false); }
+    else if (mode == 3) { if (G > 1) USL_BW(LPT == 1 ? 0 : 3, true); else USL_BW(LPT == 1 ? 0 : 3, false); }
     else if (mode == 2) { if (G > 1) USL_BW(LPT == 1 ? 2 : 0, true); else USL_BW(LPT == 1 ? 2 : 0, false); }
     else { if (G > 1) USL_BW(0, true); else USL_BW(0, false); }
 #undef USL_BW

@@ -10,7 +10,8 @@ namespace usl_products {
 // global_load_lds_dwordx4: each wavefront moves 1 KiB per instruction straight into LDS (the LDS
 // address is wave-uniform, the hardware adds lane*16), no VGPRs are used and all of a lane's loads
 // are in flight together.  The caller's barrier follows the vmcnt wait.
-template <typename TS, int NT>
+// WAIT = false leaves the copies in flight: the caller waits (vmcnt) before its barrier.
+template <typename TS, int NT, bool WAIT = true>
 __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict__ lds, int n,
                                       bool vec_ok) {
     if (vec_ok) {
@@ -24,7 +25,7 @@ __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict
                 (const __attribute__((address_space(1))) void*)(s + v + lane),
                 (__attribute__((address_space(3))) void*)(dd + v), 16, 0, 0);
         for (int v = full + threadIdx.x; v < nv; v += NT) dd[v] = s[v];
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (WAIT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else {
         for (int c = threadIdx.x; c < n; c += NT) lds[c] = src[c];
     }
