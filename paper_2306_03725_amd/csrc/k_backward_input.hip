@@ -278,7 +278,7 @@ k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, in
 
 // One launch per label window: launch boundaries are what keeps all workgroups of an XCD inside the
 // same window (a single persistent sweep, with or without a soft pacing counter, drifted apart and
-// lost the L2 reuse -- measured slower).  blockIdx.x = tile of 32 instances (fastest, so that a
+// lost the L2 reuse -- measured slower).  blockIdx.x = tile of 32 instances within the launch's 8 (fastest, so that a
 // tile stays on one XCD), blockIdx.y = block of 32 features; lanes 8g..8g+7 of a wavefront walk the
 // list of one feature, lane l of the group owns instances 4l..4l+3 of the tile.
 __global__ void __launch_bounds__(256)
@@ -286,7 +286,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ ptr /* this window's d+1 offsets, by rank */,
                    const uint32_t* __restrict__ order /* this window's features by falling list length */,
                    const uint32_t* __restrict__ slot, int k, int kshift /* log2 k, or -1 */,
-                   float* __restrict__ gxT, int d,
+                   float* __restrict__ gxT, int d, int tile0,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
                    int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
     const int rank = blockIdx.y * 32 + (threadIdx.x >> 3);
@@ -295,12 +295,13 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
     auto label_of = [&](uint32_t e) -> int32_t { return (int32_t)(kshift >= 0 ? e >> kshift : e / (uint32_t)k); };
     uint32_t p = ptr[rank];
     const uint32_t p1 = ptr[rank + 1];
-    const float* col = gT + (size_t)blockIdx.x * m * 32 + (threadIdx.x & 7) * 4;
+    const int tile = tile0 + (int)blockIdx.x;
+    const float* col = gT + (size_t)tile * m * 32 + (threadIdx.x & 7) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     // Mostly-zero gradient (decided on the device from the cell count, the same for every lane):
     // look the piece up in the flag table first and fetch only pieces that hold something.
     if (*nz_cells < sparse_below) {
-        const uint8_t* fl = nzf + (size_t)blockIdx.x * m;
+        const uint8_t* fl = nzf + (size_t)tile * m;
         const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
         for (; p < p1; p += 8) {   // lane s of the group looks entry s up; the group then visits the live ones
             const uint32_t pp = min(p + sub, p1 - 1);
@@ -357,7 +358,7 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             p = pn;
         }
     }
-    float4* dst = reinterpret_cast<float4*>(gxT + ((size_t)blockIdx.x * d + c) * 32 + (threadIdx.x & 7) * 4);
+    float4* dst = reinterpret_cast<float4*>(gxT + ((size_t)tile * d + c) * 32 + (threadIdx.x & 7) * 4);
     if (accumulate) {
         const float4 o = *dst;
         acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
@@ -468,12 +469,15 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
     const uint32_t sparse_below = (uint32_t)(cells / 2 > 0xFFFFFFFFull ? 0xFFFFFFFFull : cells / 2);
     {
-        dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
-        for (int w = 0; w < nwin; ++w)
-            hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
-                               c->k, kshift, c->gxT, c->d,
-                               w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+        // 8 tiles per launch, one per XCD: with more, an XCD's L2 would have to hold several window slices
+        for (int t0 = 0; t0 < ntile; t0 += 8) {
+            dim3 grid((unsigned)(ntile - t0 < 8 ? ntile - t0 : 8), (unsigned)((c->d + 31) / 32));
+            for (int w = 0; w < nwin; ++w)
+                hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                                   c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                                   c->k, kshift, c->gxT, c->d, t0,
+                                   w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+        }
     }
     {
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
