@@ -165,7 +165,7 @@ usl_status usl_build_slot_order(usl_ctx* c, const int32_t* idx) {
     }
     const int shift = c->storage == USL_F32 ? 0 : 1;  // two bfloat16 columns share a bank word
     int rounds = 3;
-    if (const char* e = getenv("USL_TUNE_SWEEPS")) rounds = atoi(e);   // 0 = slots in stored order
+    if (const char* e = getenv("USL_TUNE_ROUNDS")) rounds = atoi(e);   // 0 = slots in stored order
     const int64_t groups = (c->m + 31) / 32;
     const unsigned grid = (unsigned)((groups + SCHED_GROUPS - 1) / SCHED_GROUPS);
     if (rounds <= 0) {
