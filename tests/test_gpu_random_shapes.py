@@ -85,3 +85,38 @@ def test_random_shape(orc, m, d, k, b, storage):
         rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))
         assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre) + 1e-4 * rms).all()
     L.close()
+
+
+@pytest.mark.parametrize("m,d,k,b,storage", [(3001, 1000, 32, 37, "f32"), (790001, 256, 32, 3, "f32"), (2500, 4096, 64, 6, "bf16"),
+                                             (300001, 33000, 32, 2, "f32"), (1024, 64, 8, 16, "f32")])
+def test_repeated_calls_are_bit_identical(m, d, k, b, storage):
+    """Forward, the losses and (without a batch split) backward-weight fix the order of every sum: repeated
+    calls on the same inputs must agree bit for bit.  A data race between wavefronts shows up here."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=min(3, m), index=140)
+    idx, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
+    off, lab = wl.gen_targets(cfg)
+    L = usl.Layer(m, d, k, b, storage)
+    d_idx, d_W, d_x, d_g, d_off, d_lab = gu.dev(idx), gu.dev(W), gu.dev(x), gu.dev(g), gu.dev(off), gu.dev(lab)
+    ref = None
+    for rep in range(6):
+        out, gW, g2, loss = gu.empty((b, m)), gu.empty((m, k)), gu.empty((b, m)), gu.empty((1,))
+        if rep % 2:      # perturb the timing between repetitions
+            torch.empty(1 << 22, device="cuda").normal_()
+        L.forward(d_x, d_idx, d_W, out, b)
+        L.sqh_loss_grad(out, d_off, d_lab, 0.5, g2, loss, b)
+        L.backward_weight(d_g, d_x, d_idx, gW, b)
+        got = (gu.host(out).view(np.uint32), gu.host(g2).view(np.uint32), float(loss.item()))
+        gw_bits = gu.host(gW).view(np.uint32)
+        if ref is None:
+            ref, ref_gw = got, gw_bits
+        else:
+            np.testing.assert_array_equal(got[0], ref[0])
+            np.testing.assert_array_equal(got[1], ref[1])
+            assert got[2] == ref[2]
+            # a batch split (few label blocks) adds partial sums atomically: order free, values close
+            if np.array_equal(gw_bits, ref_gw):
+                continue
+            a, r = gw_bits.view(np.float32), ref_gw.view(np.float32)
+            assert_close(a, r, 1e-5, "grad_W across repetitions")
