@@ -30,6 +30,8 @@ SHAPES = draw_shapes(24) + [
     # enough labels for the register-resident kernels (several labels per lane), irregular everything else
     (300001, 257, 32, 2, "f32"), (262145, 33000, 16, 1, "f32"), (270003, 20000, 8, 3, "bf16"),
     (280000, 64, 64, 2, "bf16"), (263000, 16384, 32, 2, "bf16"), (290001, 9000, 64, 1, "f32"),
+    # rows gathered in two slices: the slice-aware slot order with every register-resident fan-in
+    (600, 40000, 64, 3, "f32"), (270001, 65536, 8, 1, "f32"), (5000, 50001, 16, 2, "f32"), (264000, 33000, 32, 2, "f32"),
 ]
 
 
