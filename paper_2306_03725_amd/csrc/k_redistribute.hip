@@ -77,19 +77,42 @@ k_sel_hist(const TS* __restrict__ W, size_t N, uint32_t* st, int shift, int bits
         if (h[i]) atomicAdd(&st[i], h[i]);
 }
 
-// picks the digit in which the running count crosses the remaining count; clears the histogram
-__global__ void k_sel_pick(uint32_t* st, int bits) {
-    if (threadIdx.x == 0) {
-        uint32_t remain = st[ST_REMAIN], cum = 0;
-        const int nb = 1 << bits;
-        int bin = nb - 1;
-        for (int i = 0; i < nb; ++i) {
-            const uint32_t hcount = st[i];
-            if (cum + hcount >= remain) { bin = i; break; }
+// picks the digit in which the running count crosses the remaining count; clears the histogram.
+// One block of 256 lanes: each sums a run of consecutive bins, a scan over the lanes finds the run that holds
+// the crossing, and that lane walks its few bins.
+__global__ void __launch_bounds__(256) k_sel_pick(uint32_t* st, int bits) {
+    __shared__ uint32_t run_sum[256];
+    const int nb = 1 << bits;
+    const int per = (nb + 255) / 256;             // at most SEL_BINS / 256
+    const int first = (int)threadIdx.x * per;
+    uint32_t mine = 0;
+    for (int q = 0; q < per; ++q)
+        if (first + q < nb) mine += st[first + q];
+    run_sum[threadIdx.x] = mine;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {           // inclusive scan
+        const uint32_t v = threadIdx.x >= (unsigned)o ? run_sum[threadIdx.x - o] : 0u;
+        __syncthreads();
+        run_sum[threadIdx.x] += v;
+        __syncthreads();
+    }
+    const uint32_t remain = st[ST_REMAIN], prefix = st[ST_PREFIX];
+    const uint32_t before = run_sum[threadIdx.x] - mine;
+    const uint32_t total = run_sum[255];
+    __syncthreads();
+    if (before < remain && before + mine >= remain) {
+        uint32_t cum = before;
+        int bin = first;
+        for (int q = 0; q < per; ++q) {
+            const uint32_t hcount = st[first + q];
+            if (cum + hcount >= remain) { bin = first + q; break; }
             cum += hcount;
         }
-        st[ST_PREFIX] = (st[ST_PREFIX] << bits) | (uint32_t)bin;
+        st[ST_PREFIX] = (prefix << bits) | (uint32_t)bin;
         st[ST_REMAIN] = remain - cum;  // = how many keys equal to the final prefix must go
+    } else if (threadIdx.x == 0 && total < remain) {   // cannot happen for a consistent histogram
+        st[ST_PREFIX] = (prefix << bits) | (uint32_t)(nb - 1);
+        st[ST_REMAIN] = remain - total;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < SEL_BINS; i += blockDim.x) st[i] = 0;
