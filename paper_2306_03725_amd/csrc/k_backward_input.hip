@@ -394,7 +394,8 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
         c->csc_win_labels = wl;
     }
     const unsigned cchunks = (unsigned)((c->d + CSC_CHUNK - 1) / CSC_CHUNK);
-    int splits = (int)((2 * (size_t)c->num_cu + nwin * cchunks - 1) / (nwin * cchunks));
+    // a workgroup fills a compute unit (1024 lanes, up to 128 KiB of LDS): as many shares as give one full round
+    int splits = (int)((size_t)c->num_cu / (nwin * cchunks));
     splits = splits < 1 ? 1 : splits > 16 ? 16 : splits;
     const dim3 cgrid((unsigned)(nwin * splits), cchunks);
     const size_t clds = (size_t)(c->d < CSC_CHUNK ? c->d : CSC_CHUNK) * 4;
