@@ -87,14 +87,11 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
             if (i + 1 < i_end)
                 stage<TS, NT, false>(x + (size_t)(i + 1) * d, lds + (size_t)((i + 1 - i_begin) & 1) * tg.buf_stride, d,
                                      tg.vec_ok);
-            if (i > i_begin) {
-#pragma unroll
-                for (int l = 0; l < LPT; ++l)
-                    if (jme + (int64_t)l * NT < m) out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
-            }
             if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d);
 #pragma unroll
             for (int l = 0; l < LPT; ++l) {
+                if (i > i_begin && jme + (int64_t)l * NT < m)   // spread over the gathers, as in the loop below
+                    out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
                 float acc = 0.f;
                 keep_packed(pk[l]);
 #pragma unroll
@@ -150,14 +147,13 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                 __syncthreads();
                 stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
-                if (part == 0 && i > i_begin) {
-#pragma unroll
-                    for (int l = 0; l < LPT; ++l)
-                        if (jme + (int64_t)l * NT < m) out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
-                }
                 if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
+                    // one score of the previous instance leaves between two labels' gathers: four stores
+                    // in a row would hold the wavefront at the memory pipeline before it starts to gather
+                    if (part == 0 && i > i_begin && jme + (int64_t)l * NT < m)
+                        out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
