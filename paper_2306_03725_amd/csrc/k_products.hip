@@ -212,7 +212,8 @@ k_forward_generic(const TS* __restrict__ x, const int32_t* __restrict__ idx,
 }
 
 // ---------------------------------------------------------------------------- weight gradient
-template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC>
+// SKIP = false leaves the zero-skipping out (callers that know the gradient is dense, e.g. after BCE).
+template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC, bool SKIP>
 __global__ void __launch_bounds__(NT)
 k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m, int d,
@@ -348,13 +349,18 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             // workgroup-wide OR through one word per wavefront behind the row buffer (two sets,
             // alternating, so the next instance's writers cannot overtake this instance's readers);
             // the barrier is the one that frees the row buffer anyway
-            uint32_t* wf = live_flags + (i & 1) * (NT / 64);
-            const bool wave_any = __any(any);
-            if ((threadIdx.x & 63) == 0) wf[threadIdx.x >> 6] = wave_any ? 1u : 0u;
-            __syncthreads();
-            uint32_t live = 0;
+            uint32_t live = 1;
+            if (SKIP) {
+                uint32_t* wf = live_flags + (i & 1) * (NT / 64);
+                const bool wave_any = __any(any);
+                if ((threadIdx.x & 63) == 0) wf[threadIdx.x >> 6] = wave_any ? 1u : 0u;
+                __syncthreads();
+                live = 0;
 #pragma unroll
-            for (int q = 0; q < NT / 64; ++q) live |= wf[q];
+                for (int q = 0; q < NT / 64; ++q) live |= wf[q];
+            } else {
+                __syncthreads();
+            }
 #pragma unroll
             for (int l = 0; l < LPT; ++l) {
                 const int64_t j = jme + (int64_t)l * NT;
@@ -372,7 +378,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
-                    if (!__any(gv[l] != 0.f)) continue;
+                    if (SKIP && !__any(gv[l] != 0.f)) continue;
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
@@ -533,7 +539,7 @@ usl_status run_forward_generic(usl_ctx* c, const void* x, const int32_t* idx, co
 
 template <int K, int LPT, int NT, typename TS>
 usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const int32_t* idx,
-                               float* grad_W, int b) {
+                               float* grad_W, int b, bool dense) {
     const int64_t nblk = (c->m + (int64_t)NT * LPT - 1) / ((int64_t)NT * LPT);
     size_t lds;
     int G;
@@ -546,11 +552,17 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
         hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W,
                            (size_t)c->m * c->k);
     }
-#define USL_BW(MODE, AT)                                                                       \
-    do {                                                                                       \
-        USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT>, lds));               \
-        hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT>), grid, dim3(NT), lds, \
-                           c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);  \
+#define USL_BW(MODE, AT)                                                                                \
+    do {                                                                                                \
+        if (dense && MODE == 0) {                                                                       \
+            USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, false>, lds));             \
+            hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, false>), grid, dim3(NT), lds, \
+                               c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);       \
+        } else {                                                                                        \
+            USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, true>, lds));              \
+            hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, true>), grid, dim3(NT), lds, \
+                               c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);       \
+        }                                                                                               \
     } while (0)
     const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : (tg.buf_stride && LPT > 1 ? 3 : 0));
     if (mode == 1) { if (G > 1) USL_BW(1, true); else USL_BW(1, false); }
@@ -606,17 +618,17 @@ usl_status forward_t(usl_ctx* c, const void* x, const int32_t* idx, const void* 
 }
 
 template <typename TS>
-usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const int32_t* idx,
+usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const int32_t* idx, bool dense,
                              float* grad_W, int b) {
     if (!fast_path_ok(c, idx, nullptr) || (uintptr_t)grad_W % 16 != 0)
         return run_backward_weight_generic<TS>(c, g, x, idx, grad_W, b);
     const bool big = c->m >= (int64_t)c->num_cu * 1024;
     switch (c->k) {
-        case 8:  return big ? run_backward_weight<8, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b);
-        case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b);
+        case 8:  return big ? run_backward_weight<8, 8, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
+        case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
         case 32:
-            return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b);
-        default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b);
+            return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
+        default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
     }
 }
 
@@ -629,7 +641,7 @@ usl_status usl_launch_forward(usl_ctx* c, const void* x, const int32_t* idx, con
 }
 
 usl_status usl_launch_backward_weight(usl_ctx* c, const float* g, const void* x,
-                                      const int32_t* idx, float* grad_W, int32_t b) {
-    return c->storage == USL_F32 ? backward_weight_t<float>(c, g, x, idx, grad_W, b)
-                                 : backward_weight_t<uint16_t>(c, g, x, idx, grad_W, b);
+                                      const int32_t* idx, float* grad_W, int32_t b, bool dense) {
+    return c->storage == USL_F32 ? backward_weight_t<float>(c, g, x, idx, dense, grad_W, b)
+                                 : backward_weight_t<uint16_t>(c, g, x, idx, dense, grad_W, b);
 }

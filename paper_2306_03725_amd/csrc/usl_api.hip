@@ -296,11 +296,11 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
         uint64_t sampled = 0;
         USL_TRY(usl_bwd_input_prepare(c, idx, b));
         USL_TRY(usl_launch_loss_tiles(c, loss_kind, g, tgt_off, tgt_lab, scale, loss, b, &sampled));
-        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b));
+        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0));   // BCE gradients are dense
         USL_TRY(usl_bwd_input_run(c, W, grad_x, b, sampled));
     } else {
         USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
-        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b));
+        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0));   // BCE gradients are dense
     }
     const double c1 = 1.0 - pow((double)beta1, (double)t);
     const double c2 = 1.0 - pow((double)beta2, (double)t);

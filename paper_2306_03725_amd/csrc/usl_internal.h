@@ -77,8 +77,9 @@ usl_status usl_build_slot_order(usl_ctx* ctx, const int32_t* idx);
 // Kernel launchers (one per file).  All take validated arguments.
 usl_status usl_launch_forward(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W,
                               float* out, int32_t b);
+// dense = the caller knows that g holds (almost) no exact zeros: the zero-skipping tests are left out
 usl_status usl_launch_backward_weight(usl_ctx* ctx, const float* g, const void* x,
-                                      const int32_t* idx, float* grad_W, int32_t b);
+                                      const int32_t* idx, float* grad_W, int32_t b, bool dense = false);
 usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx,
                                      const void* W, float* grad_x, int32_t b);
 // backward_input in two halves, for callers that produce gT / nz_flags / the nonzero count themselves
