@@ -61,9 +61,11 @@ usl_status usl_create(usl_ctx** ctx, int64_t m, int32_t d, int32_t k, int32_t ma
                       usl_dtype storage, void* hip_stream);
 usl_status usl_destroy(usl_ctx* ctx); /* frees the context and its device scratch; NULL is OK */
 usl_status usl_set_stream(usl_ctx* ctx, void* hip_stream);
-/* The library keeps a column-major copy of the connectivity for usl_backward_input, keyed by the
- * idx pointer and rebuilt after usl_init_indices / usl_redistribute.  A caller that rewrites the
- * contents of idx by any other means must call this before the next usl_backward_input. */
+/* The library keeps private views of the connectivity (a column-major copy for usl_backward_input,
+ * a per-label visiting order of the slots for the two other products), keyed by the idx pointer and
+ * rebuilt after usl_init_indices / usl_redistribute / usl_redistribute_rows.  A caller that rewrites
+ * the contents of idx by any other means must call this before the next product call: a stale
+ * column-major copy gives wrong input gradients (a stale visiting order only costs speed). */
 usl_status usl_invalidate(usl_ctx* ctx);
 const char* usl_last_error(const usl_ctx* ctx); /* never NULL; owned by the context */
 const char* usl_version(void);
