@@ -109,6 +109,12 @@ usl_status usl_sqh_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_
 usl_status usl_topk(usl_ctx* ctx, const float* out, int32_t b, int32_t kk, int32_t* top_lab,
                     float* top_val);
 
+/* Prediction from the activations (Section 2: yhat = top_k(W^T psi(x))): usl_forward followed by usl_topk,
+ * 64 instances at a time through library scratch, so the [b][m] scores are never laid out in full.
+ * Arguments and results as for those two calls. */
+usl_status usl_predict(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W, int32_t b,
+                       int32_t kk, int32_t* top_lab, float* top_val);
+
 /* Precision at k (Section 2, the equation defining P@k = (1/k) sum_j y_j yhat_j): hits[r], r < kk,
  * is set to the number of instances i < b whose rank-r prediction top_lab[i][r] is one of the
  * instance's targets (a set: repeats count once), so P@k = (hits[0]+...+hits[k-1]) / (k*b) for every

@@ -31,7 +31,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
-                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W};
+                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
@@ -156,6 +156,28 @@ extern "C" usl_status usl_topk(usl_ctx* c, const float* out, int32_t b, int32_t 
         USL_FAIL(c, USL_ESHAPE, "kk = %d, this build takes at most min(m, %d)", kk, usl_topk_max());
     USL_TRY(usl_prepare_device(c));
     return usl_launch_topk(c, out, b, kk, top_lab, top_val);
+}
+
+extern "C" usl_status usl_predict(usl_ctx* c, const void* x, const int32_t* idx, const void* W, int32_t b,
+                                  int32_t kk, int32_t* top_lab, float* top_val) {
+    if (!c) return USL_EINVAL;
+    NEED(x); NEED(idx); NEED(W); NEED(top_lab); NEED(top_val);
+    USL_TRY(check_batch(c, b));
+    if (kk < 1) USL_FAIL(c, USL_EINVAL, "kk = %d, must be at least 1", kk);
+    if (kk > c->m || kk > usl_topk_max())
+        USL_FAIL(c, USL_ESHAPE, "kk = %d, this build takes at most min(m, %d)", kk, usl_topk_max());
+    USL_TRY(usl_prepare_device(c));
+    // scores of 64 instances at a time: the chunk (256 B per label) is consumed while it is still in the
+    // caches, and no [b][m] array is ever needed
+    const int chunk = b < 64 ? b : 64;
+    USL_TRY(usl_reserve(c, (void**)&c->predict_out, &c->predict_out_cap, (size_t)chunk * c->m * 4));
+    const size_t xrow = (size_t)c->d * (c->storage == USL_F32 ? 4 : 2);
+    for (int i0 = 0; i0 < b; i0 += chunk) {
+        const int n = b - i0 < chunk ? b - i0 : chunk;
+        USL_TRY(usl_launch_forward(c, (const char*)x + (size_t)i0 * xrow, idx, W, c->predict_out, n));
+        USL_TRY(usl_launch_topk(c, c->predict_out, n, kk, top_lab + (size_t)i0 * kk, top_val + (size_t)i0 * kk));
+    }
+    return USL_OK;
 }
 
 extern "C" usl_status usl_precision_hits(usl_ctx* c, const int32_t* top_lab, const int64_t* tgt_off,

@@ -17,7 +17,7 @@ STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", 
 # every symbol include/usl.h declares
 SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
-           "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows",
+           "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows", "usl_predict",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
            "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
@@ -40,6 +40,7 @@ _sig = {
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_topk": [_vp, _vp, _i32, _i32, _vp, _vp],
+    "usl_predict": [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp],
     "usl_train_step": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _i64, _f32, _f32, _f32, _f32,
                        _vp, _vp, _vp, _vp, _i32],
     "usl_forward_rows": [_vp, _vp, _vp, _vp, _vp, _i64, _vp, _i32],
@@ -142,6 +143,9 @@ class Layer:
 
     def topk(self, out, b, kk, top_lab, top_val):
         self._ck(_lib.usl_topk(self._h, _ptr(out), b, kk, _ptr(top_lab), _ptr(top_val)))
+
+    def predict(self, x, idx, W, b, kk, top_lab, top_val):
+        self._ck(_lib.usl_predict(self._h, _ptr(x), _ptr(idx), _ptr(W), b, kk, _ptr(top_lab), _ptr(top_val)))
 
     def precision_hits(self, top_lab, tgt_off, tgt_lab, b, kk, hits):
         self._ck(_lib.usl_precision_hits(self._h, _ptr(top_lab), _ptr(tgt_off), _ptr(tgt_lab), b, kk,

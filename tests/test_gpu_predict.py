@@ -104,3 +104,25 @@ def test_topk_argument_errors(usl, gu):
         assert e.value.status == status
     with pytest.raises(usl.UslError):
         L.topk(out, 5, 3, lab, val)              # batch beyond max_b
+
+
+@pytest.mark.parametrize("m,d,k,b,kk,storage", [(1024, 64, 8, 16, 5, "f32"), (30938, 1024, 32, 70, 3, "f32"),
+                                                (3001, 1000, 32, 37, 32, "bf16"), (270001, 2048, 32, 33, 5, "f32"),
+                                                (500, 203, 5, 65, 1, "f32")])
+def test_predict_is_forward_then_topk(usl, gu, orc, m, d, k, b, kk, storage):
+    """usl_predict (scores 64 instances at a time, never laid out in full) against the oracle's top-k of the
+    scores the forward call writes, and those scores against the oracle's."""
+    from helpers import assert_close
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=1, index=150)
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    L = usl.Layer(m, d, k, b, storage)
+    d_idx, d_W, d_x = gu.dev(idx), gu.dev(W), gu.dev(x)
+    lab, val = gu.empty((b, kk), torch.int32).fill_(-1), gu.empty((b, kk)).fill_(float("nan"))
+    L.predict(d_x, d_idx, d_W, b, kk, lab, val)
+    out = gu.empty((b, m))
+    L.forward(d_x, d_idx, d_W, out, b)
+    scores = gu.host(out)
+    assert_close(scores, orc.forward(x, idx, W), 1e-5, "scores")
+    ref_lab, ref_val = orc.topk(scores, kk)
+    np.testing.assert_array_equal(gu.host(lab), ref_lab)
+    np.testing.assert_array_equal(gu.host(val).view(np.uint32), ref_val.view(np.uint32))
