@@ -76,6 +76,16 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
     if (MODE == 3) {
+        // two bfloat16 rows fit only if the row has at most 32768 columns: a column's byte offset then fits
+        // the 16 bits of a packed index, and the gathers save the scaling (they are bound by vector
+        // instructions, not by LDS, on bfloat16 rows)
+        constexpr bool SCALED = sizeof(TS) == 2;
+        if (SCALED) {
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+#pragma unroll
+                for (int q = 0; q < K / 2; ++q) pk[l][q] <<= 1;
+        }
         float prev[LPT];
         __syncthreads();   // the transposition buffer is free
         if (i_begin < i_end) stage<TS, NT>(x + (size_t)i_begin * d, lds, d, tg.vec_ok);
@@ -96,7 +106,7 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                 keep_packed(pk[l]);
 #pragma unroll
                 for (int t = 0; t < K; ++t) {
-                    acc = fmaf(w[l][t], lds_val(cur, col_of<K>(pk[l], t)), acc);
+                    acc = fmaf(w[l][t], SCALED ? lds_at(cur, col_of<K>(pk[l], t)) : lds_val(cur, col_of<K>(pk[l], t)), acc);
                     if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                 }
                 asm volatile("" : "+v"(acc));
@@ -244,6 +254,13 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
     const int i_begin = blockIdx.y * tg.inst_per_group;
     const int i_end = min(b, i_begin + tg.inst_per_group);
     if (MODE == 3) {
+        constexpr bool SCALED = sizeof(TS) == 2;   // byte offsets in the packed indices, as in the forward kernel
+        if (SCALED) {
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+#pragma unroll
+                for (int q = 0; q < K / 2; ++q) pk[l][q] <<= 1;
+        }
         // as in the single-buffer loop below, an instance (a label group) whose gradients are all zero skips
         // its gathers; the row copy is not skipped, it runs one instance ahead
         uint32_t* live_flags = reinterpret_cast<uint32_t*>(lds_raw + tg.flag_offset);
@@ -288,7 +305,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
-                        acc[l][t] = fmaf(gv[l], lds_val(cur, col_of<K>(pk[l], t)), acc[l][t]);
+                        acc[l][t] = fmaf(gv[l], SCALED ? lds_at(cur, col_of<K>(pk[l], t)) : lds_val(cur, col_of<K>(pk[l], t)), acc[l][t]);
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                     }
                 }

@@ -31,6 +31,13 @@ __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict
     }
 }
 
+// The same with the byte offset of the element instead of its column (indices scaled once, outside the loop).
+__device__ __forceinline__ float lds_at(const float* row, uint32_t byte_off) {
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + byte_off);
+}
+__device__ __forceinline__ float lds_at(const uint16_t* row, uint32_t byte_off) {
+    return usl_bf16_to_f32(*reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(row) + byte_off));
+}
 __device__ __forceinline__ float lds_val(const float* row, uint32_t c) { return row[c]; }
 __device__ __forceinline__ float lds_val(const uint16_t* row, uint32_t c) {
     return usl_bf16_to_f32(row[c]);
