@@ -338,7 +338,16 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             for (int q = 0; q < U; ++q) j[q] = __shfl(jm, gl + q);
             float4 v[U];
 #pragma unroll
-            for (int q = 0; q < U; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
+            for (int q = 0; q < U / 2; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
+            // the second half of a trip is not even requested when the list ends before it (lists of one
+            // wavefront are of nearly one length, so the instruction is then skipped by the whole wavefront)
+            if (p + U / 2 < p1) {
+#pragma unroll
+                for (int q = U / 2; q < U; ++q) v[q] = *reinterpret_cast<const float4*>(col + (size_t)j[q] * 32);
+            } else {
+#pragma unroll
+                for (int q = U / 2; q < U; ++q) v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
             float w[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) w[q] = __shfl(wm, gl + q);
