@@ -86,6 +86,17 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
 #pragma unroll
                 for (int q = 0; q < K / 2; ++q) pk[l][q] <<= 1;
         }
+        // bfloat16: the weights go back to pairs (they are exact bfloat16 values), two gathered activations are
+        // joined into one register, and one dot-product instruction does both multiply-adds in float32
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        uint32_t wp[SCALED ? LPT : 1][SCALED ? K / 2 : 1];
+        if (SCALED) {
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+#pragma unroll
+                for (int q = 0; q < K / 2; ++q)
+                    wp[l][q] = (__float_as_uint(w[l][2 * q]) >> 16) | (__float_as_uint(w[l][2 * q + 1]) & 0xFFFF0000u);
+        }
         float prev[LPT];
         __syncthreads();   // the transposition buffer is free
         if (i_begin < i_end) stage<TS, NT>(x + (size_t)i_begin * d, lds, d, tg.vec_ok);
@@ -104,10 +115,23 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                     out[(size_t)(i - 1) * m + jme + (int64_t)l * NT] = prev[l];
                 float acc = 0.f;
                 keep_packed(pk[l]);
+                if (SCALED) {
+                    const char* base = reinterpret_cast<const char*>(cur);
 #pragma unroll
-                for (int t = 0; t < K; ++t) {
-                    acc = fmaf(w[l][t], SCALED ? lds_at(cur, col_of<K>(pk[l], t)) : lds_val(cur, col_of<K>(pk[l], t)), acc);
-                    if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                    for (int q = 0; q < K / 2; ++q) {
+                        const uint32_t lo = *reinterpret_cast<const uint16_t*>(base + (pk[l][q] & 0xFFFFu));
+                        const uint32_t hi = *reinterpret_cast<const uint16_t*>(base + (pk[l][q] >> 16));
+                        const uint32_t pair = lo | (hi << 16);
+                        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair),
+                                                              __builtin_bit_cast(bf16x2, wp[SCALED ? l : 0][SCALED ? q : 0]), acc, false);
+                        if ((q & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < K; ++t) {
+                        acc = fmaf(w[l][t], lds_val(cur, col_of<K>(pk[l], t)), acc);
+                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
                 asm volatile("" : "+v"(acc));
                 prev[l] = acc;
