@@ -232,3 +232,7 @@ def test_large_train_step_squared_hinge_full_size(orc):
 
 def test_large_wide_train_step_full_size(orc):
     run_full_train_step(wl.CONFIGS["large_wide"], orc, 0, n_lab=2048, n_inst=2)
+
+
+def test_stress_train_step_full_size(orc):
+    run_full_train_step(wl.CONFIGS["stress"], orc, 0, n_lab=1024, n_inst=2)
