@@ -653,7 +653,12 @@ usl_status forward_t(usl_ctx* c, const void* x, const int32_t* idx, const void* 
         case 8:  return big ? run_forward<8, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<8, 1, 256, TS>(c, x, idx, W, out, b);
         case 16: return big ? run_forward<16, 8, 512, TS>(c, x, idx, W, out, b) : run_forward<16, 1, 256, TS>(c, x, idx, W, out, b);
         case 32:
-            return big ? run_forward<32, 4, 512, TS>(c, x, idx, W, out, b) : run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
+            // float32: 1024 lanes with two labels each keep twice the wavefronts of 512 x 4 on a
+            // compute unit that the row buffer limits to one workgroup, within the 128 registers
+            // such a workgroup leaves each lane; the bfloat16 variant would spill there.
+            if (!big) return run_forward<32, 1, 256, TS>(c, x, idx, W, out, b);
+            if constexpr (sizeof(TS) == 4) return run_forward<32, 2, 1024, TS>(c, x, idx, W, out, b);
+            else return run_forward<32, 4, 512, TS>(c, x, idx, W, out, b);
         default: return big ? run_forward<64, 2, 512, TS>(c, x, idx, W, out, b) : run_forward<64, 1, 256, TS>(c, x, idx, W, out, b);
     }
 }
