@@ -21,13 +21,14 @@ namespace {
 // the whole chip waits out an HBM round trip per row.  Workgroups are dealt to the 8 XCDs round
 // robin; those of one XCD share the row between them, one load per 128-byte line.
 template <typename TS>
-__device__ __forceinline__ void prefetch_row_slice(const TS* __restrict__ row, int n) {
+__device__ __forceinline__ void prefetch_row_slice(const TS* __restrict__ row, int n,
+                                                   int tid = (int)threadIdx.x) {
     const int lines = (int)(((size_t)n * sizeof(TS) + 127) / 128);
     const int nsl = max(1, (int)(gridDim.x >> 3));
     const int sl = (int)(blockIdx.x >> 3) % nsl;
     const int per = (lines + nsl - 1) / nsl;
-    const int line = sl * per + (int)threadIdx.x;
-    if ((int)threadIdx.x < per && line < lines)
+    const int line = sl * per + tid;
+    if (tid < per && line < lines)
         (void)*reinterpret_cast<const volatile uint32_t*>(reinterpret_cast<const char*>(row) + (size_t)line * 128);
 }
 
@@ -381,8 +382,15 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
         // with a short row the flag words lie inside the buffer the indices were transposed through:
         // every wavefront must have picked up its indices before the first flag is written
         __syncthreads();
+        // labels of this workgroup that exist; the gradient loads address them with 32-bit offsets
+        const int nlab = (int)min((int64_t)NT * LPT, m - j0);
 #pragma unroll 1
         for (int i = i_begin; i < i_end; ++i) {
+            // the lane number is taken afresh every instance: addresses derived from it (row copy,
+            // warm-up, gradient loads) are then rebuilt with a few instructions each time round
+            // instead of living in a dozen registers across the gathers, which need them more
+            int tid = (int)threadIdx.x;
+            asm volatile("" : "+v"(tid));
             float gv[LPT];
             bool any = false;
 #pragma unroll
@@ -394,7 +402,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             if (SKIP) {
                 uint32_t* wf = live_flags + (i & 1) * (NT / 64);
                 const bool wave_any = __any(any);
-                if ((threadIdx.x & 63) == 0) wf[threadIdx.x >> 6] = wave_any ? 1u : 0u;
+                if ((tid & 63) == 0) wf[tid >> 6] = wave_any ? 1u : 0u;
                 __syncthreads();
                 live = 0;
 #pragma unroll
@@ -402,10 +410,13 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             } else {
                 __syncthreads();
             }
+            {
+                const float* gr = g + (size_t)(i + 1) * m + j0;
 #pragma unroll
-            for (int l = 0; l < LPT; ++l) {
-                const int64_t j = jme + (int64_t)l * NT;
-                gnext[l] = (j < m && i + 1 < i_end) ? g[(size_t)(i + 1) * m + j] : 0.f;
+                for (int l = 0; l < LPT; ++l) {
+                    const int jl = tid + l * NT;
+                    gnext[l] = (jl < nlab && i + 1 < i_end) ? gr[jl] : 0.f;
+                }
             }
             if (!live) continue;
             const int nparts = MODE == 1 ? tg.nparts : 1;
@@ -414,9 +425,9 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 const int c0 = part * tg.part_cols;
                 const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
                 if (part > 0) __syncthreads();
-                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
+                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok, tid);
                 __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
+                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tid);
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     if (SKIP && !__any(gv[l] != 0.f)) continue;
@@ -673,7 +684,15 @@ usl_status backward_weight_t(usl_ctx* c, const float* g, const void* x, const in
         case 8:  return big ? run_backward_weight<8, 8, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<8, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
         case 16: return big ? run_backward_weight<16, 8, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<16, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
         case 32:
-            return big ? run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
+            if (!big) return run_backward_weight<32, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
+            // 1024 lanes pay only for float32 rows that take the whole buffer (one workgroup per compute
+            // unit, one row at a time): measured 3 % there, nothing or a loss for sliced or paired rows
+            if constexpr (sizeof(TS) == 4) {
+                const size_t row_bytes = (size_t)c->d * 4;
+                if (row_bytes <= (size_t)USL_ROW_LDS_BYTES && 2 * row_bytes + 256 > (size_t)USL_ROW_LDS_BYTES + 8192)
+                    return run_backward_weight<32, 2, 1024, TS>(c, g, x, idx, grad_W, b, dense);
+            }
+            return run_backward_weight<32, 4, 512, TS>(c, g, x, idx, grad_W, b, dense);
         default: return big ? run_backward_weight<64, 2, 512, TS>(c, g, x, idx, grad_W, b, dense) : run_backward_weight<64, 1, 256, TS>(c, g, x, idx, grad_W, b, dense);
     }
 }

@@ -13,21 +13,21 @@ namespace usl_products {
 // WAIT = false leaves the copies in flight: the caller waits (vmcnt) before its barrier.
 template <typename TS, int NT, bool WAIT = true>
 __device__ __forceinline__ void stage(const TS* __restrict__ src, TS* __restrict__ lds, int n,
-                                      bool vec_ok) {
+                                      bool vec_ok, int tid = (int)threadIdx.x) {
     if (vec_ok) {
         const uint4* s = reinterpret_cast<const uint4*>(src);
         uint4* dd = reinterpret_cast<uint4*>(lds);
         const int nv = (int)((size_t)n * sizeof(TS) / 16);
         const int full = nv & ~63;
-        const int lane = threadIdx.x & 63;
-        for (int v = (threadIdx.x >> 6) * 64; v < full; v += NT)
+        const int lane = tid & 63;
+        for (int v = (tid >> 6) * 64; v < full; v += NT)
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(s + v + lane),
                 (__attribute__((address_space(3))) void*)(dd + v), 16, 0, 0);
-        for (int v = full + threadIdx.x; v < nv; v += NT) dd[v] = s[v];
+        for (int v = full + tid; v < nv; v += NT) dd[v] = s[v];
         if (WAIT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else {
-        for (int c = threadIdx.x; c < n; c += NT) lds[c] = src[c];
+        for (int c = tid; c < n; c += NT) lds[c] = src[c];
     }
 }
 
