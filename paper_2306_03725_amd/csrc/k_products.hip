@@ -54,6 +54,7 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
           const uint8_t* __restrict__ perm) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
+    if (MODE == 0 && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
     uint32_t pk[LPT][K / 2];
     float w[LPT][K];
@@ -192,11 +193,18 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
-                        const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
-                        // sliced rows: a slot outside the slice reads a word of zeros behind it
-                        // (no branch, so the gathers stay pipelined)
-                        const uint32_t cc = (MODE == 0 || c < cols) ? c : zcol;
-                        acc[l] = fmaf(w[l][t], lds_val(lds, cc), acc[l]);
+                        float xv;
+                        if (MODE == 0 && sizeof(TS) == 4) {
+                            xv = gather_row0<K>(pk[l], t);
+                        } else if (MODE == 0) {
+                            xv = lds_val(lds, col_of<K>(pk[l], t));
+                        } else {
+                            // sliced rows: a slot outside the slice reads a word of zeros behind it
+                            // (no branch, so the gathers stay pipelined)
+                            const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
+                            xv = lds_val(lds, c < cols ? c : zcol);
+                        }
+                        acc[l] = fmaf(w[l][t], xv, acc[l]);
                         // a few gathers in flight at a time: their results would otherwise
                         // crowd out the resident indices and weights
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
@@ -255,6 +263,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   int b, TileGeom tg, const uint8_t* __restrict__ perm) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
+    if (MODE == 0 && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
     uint32_t pk[LPT][K / 2];
     float acc[LPT][K];
@@ -434,9 +443,16 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                     keep_packed(pk[l]);
 #pragma unroll
                     for (int t = 0; t < K; ++t) {
-                        const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
-                        const uint32_t cc = (MODE == 0 || c < cols) ? c : zcol;
-                        acc[l][t] = fmaf(gv[l], lds_val(lds, cc), acc[l][t]);
+                        float xv;
+                        if (MODE == 0 && sizeof(TS) == 4) {
+                            xv = gather_row0<K>(pk[l], t);
+                        } else if (MODE == 0) {
+                            xv = lds_val(lds, col_of<K>(pk[l], t));
+                        } else {
+                            const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
+                            xv = lds_val(lds, c < cols ? c : zcol);
+                        }
+                        acc[l][t] = fmaf(gv[l], xv, acc[l][t]);
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                     }
                 }

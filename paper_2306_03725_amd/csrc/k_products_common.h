@@ -122,6 +122,33 @@ __device__ __forceinline__ uint32_t col_of(const uint32_t (&pk)[K / 2], int t) {
     return (t & 1) ? (pk[t >> 1] >> 16) : (pk[t >> 1] & 0xFFFFu);
 }
 
+// Byte offset (column * 4) of slot t in a float32 row.  The 16-bit half of the packed word is
+// selected and shifted by one instruction (sub-dword operand select) where mask-and-shift takes two.
+template <int K>
+__device__ __forceinline__ uint32_t byte_off4(const uint32_t (&pk)[K / 2], int t) {
+    uint32_t a;
+    const uint32_t two = 2;
+    if (t & 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+            : "=v"(a) : "s"(two), "v"(pk[t >> 1]));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+            : "=v"(a) : "s"(two), "v"(pk[t >> 1]));
+    return a;
+}
+// Slot t of the float32 row that starts at the very beginning of the workgroup's LDS: the byte offset
+// is the LDS address itself, so no base is added (one vector instruction per gather instead of two).
+// Kernels that use it have no static LDS, which puts their dynamic LDS at address 0; they check that
+// once (lds_starts_at_zero) before relying on it.
+typedef const __attribute__((address_space(3))) float lds_f32_t;
+template <int K>
+__device__ __forceinline__ float gather_row0(const uint32_t (&pk)[K / 2], int t) {
+    return *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(byte_off4<K>(pk, t)));
+}
+__device__ __forceinline__ bool lds_starts_at_zero(const void* dyn_lds) {
+    return (uint32_t)(uintptr_t)((const __attribute__((address_space(3))) void*)dyn_lds) == 0u;
+}
+
 template <int K, int NT>
 __device__ __forceinline__ void fetch_w(const float* __restrict__ W, int64_t row0, int64_t m,
                                         uint32_t* lds, const SlotOrder<K>& so, float (&w)[K]) {
