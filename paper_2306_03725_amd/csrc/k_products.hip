@@ -254,6 +254,12 @@ k_forward_generic(const TS* __restrict__ x, const int32_t* __restrict__ idx,
     }
 }
 
+// OR of four consecutive flag words (16-byte aligned) with one LDS read.
+__device__ __forceinline__ uint32_t or4(const uint32_t* p) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    return (v.x | v.y) | (v.z | v.w);
+}
+
 // ---------------------------------------------------------------------------- weight gradient
 // SKIP = false leaves the zero-skipping out (callers that know the gradient is dense, e.g. after BCE).
 template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC, bool SKIP>
@@ -331,7 +337,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             const uint32_t* wf = live_flags + ((i - i_begin) & 1) * (NT / 64);
             uint32_t live = 0;
 #pragma unroll
-            for (int q = 0; q < NT / 64; ++q) live |= wf[q];
+            for (int q = 0; q < NT / 256; ++q) live |= or4(wf + 4 * q);
             if (live) {
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
@@ -415,7 +421,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 __syncthreads();
                 live = 0;
 #pragma unroll
-                for (int q = 0; q < NT / 64; ++q) live |= wf[q];
+                for (int q = 0; q < NT / 256; ++q) live |= or4(wf + 4 * q);
             } else {
                 __syncthreads();
             }
