@@ -110,7 +110,8 @@ usl_status usl_topk(usl_ctx* ctx, const float* out, int32_t b, int32_t kk, int32
                     float* top_val);
 
 /* Prediction from the activations (Section 2: yhat = top_k(W^T psi(x))): usl_forward followed by usl_topk,
- * 64 instances at a time through library scratch, so the [b][m] scores are never laid out in full.
+ * through scratch memory of the library (the caller never provides a [b][m] array); the scratch is held
+ * to 1 GiB, or 64 instances if those take more, and a larger batch goes through it in chunks.
  * Arguments and results as for those two calls. */
 usl_status usl_predict(usl_ctx* ctx, const void* x, const int32_t* idx, const void* W, int32_t b,
                        int32_t kk, int32_t* top_lab, float* top_val);

@@ -167,9 +167,11 @@ extern "C" usl_status usl_predict(usl_ctx* c, const void* x, const int32_t* idx,
     if (kk > c->m || kk > usl_topk_max())
         USL_FAIL(c, USL_ESHAPE, "kk = %d, this build takes at most min(m, %d)", kk, usl_topk_max());
     USL_TRY(usl_prepare_device(c));
-    // scores of 64 instances at a time: the chunk (256 B per label) is consumed while it is still in the
-    // caches, and no [b][m] array is ever needed
-    const int chunk = b < 64 ? b : 64;
+    // the scores live in a scratch array of the library, never in a [b][m] array of the caller; it is capped
+    // at 1 GiB (at least 64 instances), so a large batch goes through in chunks: fewer chunks are faster
+    // (every forward launch brings idx and W into registers again), 64 instances still amortise that well
+    const int64_t cap_rows = (int64_t)(((size_t)1 << 30) / ((size_t)c->m * 4));
+    const int chunk = (int)(b <= 64 || cap_rows >= b ? b : (cap_rows < 64 ? 64 : cap_rows));
     USL_TRY(usl_reserve(c, (void**)&c->predict_out, &c->predict_out_cap, (size_t)chunk * c->m * 4));
     const size_t xrow = (size_t)c->d * (c->storage == USL_F32 ? 4 : 2);
     for (int i0 = 0; i0 < b; i0 += chunk) {
