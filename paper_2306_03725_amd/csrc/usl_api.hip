@@ -170,7 +170,12 @@ extern "C" usl_status usl_predict(usl_ctx* c, const void* x, const int32_t* idx,
     // the scores live in a scratch array of the library, never in a [b][m] array of the caller; it is capped
     // at 1 GiB (at least 64 instances), so a large batch goes through in chunks: fewer chunks are faster
     // (every forward launch brings idx and W into registers again), 64 instances still amortise that well
-    const int64_t cap_rows = (int64_t)(((size_t)1 << 30) / ((size_t)c->m * 4));
+    size_t cap_bytes = (size_t)1 << 30;
+    if (const char* e = getenv("USL_TUNE_PREDICT_BYTES")) {   // a test aid: a small cap exercises the chunking
+        const long long v = atoll(e);
+        if (v > 0) cap_bytes = (size_t)v;
+    }
+    const int64_t cap_rows = (int64_t)(cap_bytes / ((size_t)c->m * 4));
     const int chunk = (int)(b <= 64 || cap_rows >= b ? b : (cap_rows < 64 ? 64 : cap_rows));
     USL_TRY(usl_reserve(c, (void**)&c->predict_out, &c->predict_out_cap, (size_t)chunk * c->m * 4));
     const size_t xrow = (size_t)c->d * (c->storage == USL_F32 ? 4 : 2);

@@ -110,8 +110,21 @@ def test_topk_argument_errors(usl, gu):
                                                 (3001, 1000, 32, 37, 32, "bf16"), (270001, 2048, 32, 33, 5, "f32"),
                                                 (500, 203, 5, 65, 1, "f32")])
 def test_predict_is_forward_then_topk(usl, gu, orc, m, d, k, b, kk, storage):
-    """usl_predict (scores 64 instances at a time, never laid out in full) against the oracle's top-k of the
-    scores the forward call writes, and those scores against the oracle's."""
+    """usl_predict (scores through library scratch) against the oracle's top-k of the scores the forward call
+    writes, and those scores against the oracle's."""
+    _predict_case(usl, gu, orc, m, d, k, b, kk, storage)
+
+
+def test_predict_in_chunks(usl, gu, orc, monkeypatch):
+    """A scratch cap of 70 rows: 150 instances go through as 70 + 70 + 10; a cap below 64 rows means 64."""
+    m = 30938
+    monkeypatch.setenv("USL_TUNE_PREDICT_BYTES", str(70 * m * 4))
+    _predict_case(usl, gu, orc, m, 1024, 32, 150, 5, "f32")
+    monkeypatch.setenv("USL_TUNE_PREDICT_BYTES", str(3 * m * 4))
+    _predict_case(usl, gu, orc, m, 1024, 32, 130, 2, "f32")
+
+
+def _predict_case(usl, gu, orc, m, d, k, b, kk, storage):
     from helpers import assert_close
     cfg = wl.custom(m, d, k, b, storage=storage, positives=1, index=150)
     idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
