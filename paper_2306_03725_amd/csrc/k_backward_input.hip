@@ -281,6 +281,10 @@ k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, in
 // lost the L2 reuse -- measured slower).  blockIdx.x = tile of 32 instances within the launch's 8 (fastest, so that a
 // tile stays on one XCD), blockIdx.y = block of 32 features; lanes 8g..8g+7 of a wavefront walk the
 // list of one feature, lane l of the group owns instances 4l..4l+3 of the tile.
+// SPLIT = 8 (few features, long lists: small d) gives a feature a whole wavefront: each of its 8 lane
+// groups walks a contiguous eighth of the list and the eight sums are added by lane shuffles, so a launch
+// has 8 times the workgroups and an eighth of the dependent trips.
+template <int SPLIT>
 __global__ void __launch_bounds__(256)
 k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ ptr /* this window's d+1 offsets, by rank */,
@@ -289,12 +293,18 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    float* __restrict__ gxT, int d, int tile0,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
                    int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
-    const int rank = blockIdx.y * 32 + (threadIdx.x >> 3);
-    if (rank >= d) return;
+    const int rank = SPLIT == 1 ? blockIdx.y * 32 + (threadIdx.x >> 3) : blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (rank >= d) return;   // SPLIT = 8: the whole wavefront leaves
     const int c = (int)order[rank];
     auto label_of = [&](uint32_t e) -> int32_t { return (int32_t)(kshift >= 0 ? e >> kshift : e / (uint32_t)k); };
     uint32_t p = ptr[rank];
-    const uint32_t p1 = ptr[rank + 1];
+    uint32_t p1 = ptr[rank + 1];
+    if (SPLIT > 1) {   // this lane group's share: a multiple of 8 entries, the last share takes the rest
+        const uint32_t per = ((p1 - p + SPLIT * 8 - 1) / (SPLIT * 8)) * 8;
+        const uint32_t sg = (threadIdx.x >> 3) & (SPLIT - 1);
+        p = min(p1, p + sg * per);
+        p1 = min(p1, p + per);
+    }
     const int tile = tile0 + (int)blockIdx.x;
     const float* col = gT + (size_t)tile * m * 32 + (threadIdx.x & 7) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -366,6 +376,14 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             if (pn >= p1) break;
             p = pn;
         }
+    }
+    if (SPLIT > 1) {
+#pragma unroll
+        for (int o = 8; o < 8 * SPLIT; o <<= 1) {
+            acc.x += __shfl_xor(acc.x, o); acc.y += __shfl_xor(acc.y, o);
+            acc.z += __shfl_xor(acc.z, o); acc.w += __shfl_xor(acc.w, o);
+        }
+        if (((threadIdx.x >> 3) & (SPLIT - 1)) != 0) return;
     }
     float4* dst = reinterpret_cast<float4*>(gxT + ((size_t)tile * d + c) * 32 + (threadIdx.x & 7) * 4);
     if (accumulate) {
@@ -481,12 +499,22 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
     {
         // 8 tiles per launch, one per XCD: with more, an XCD's L2 would have to hold several window slices
         for (int t0 = 0; t0 < ntile; t0 += 8) {
-            dim3 grid((unsigned)(ntile - t0 < 8 ? ntile - t0 : 8), (unsigned)((c->d + 31) / 32));
-            for (int w = 0; w < nwin; ++w)
-                hipLaunchKernelGGL(k_bwd_input_window, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                                   c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
-                                   c->k, kshift, c->gxT, c->d, t0,
-                                   w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+            const unsigned ntl = (unsigned)(ntile - t0 < 8 ? ntile - t0 : 8);
+            // too few (tile, 32 features) workgroups to fill the chip: a wavefront per feature instead
+            const bool split = (int64_t)ntl * ((c->d + 31) / 32) < 2 * (int64_t)c->num_cu;
+            dim3 grid(ntl, (unsigned)(split ? (c->d + 3) / 4 : (c->d + 31) / 32));
+            for (int w = 0; w < nwin; ++w) {
+                if (split)
+                    hipLaunchKernelGGL(k_bwd_input_window<8>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                                       c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                                       c->k, kshift, c->gxT, c->d, t0,
+                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+                else
+                    hipLaunchKernelGGL(k_bwd_input_window<1>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                                       c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                                       c->k, kshift, c->gxT, c->d, t0,
+                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+            }
         }
     }
     {
