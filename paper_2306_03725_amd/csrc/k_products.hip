@@ -266,7 +266,7 @@ template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC, bool SKIP>
 __global__ void __launch_bounds__(NT)
 k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m, int d,
-                  int b, TileGeom tg, const uint8_t* __restrict__ perm) {
+                  int b, TileGeom tg, const uint8_t* __restrict__ perm, int64_t part_stride) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
     if (MODE == 0 && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
@@ -475,7 +475,12 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
 #pragma unroll
         for (int t = 0; t < K; ++t) tr[threadIdx.x * (K + 1) + so.at(t)] = __float_as_uint(acc[l][t]);
         __syncthreads();
-        lds_to_rows<K, NT, ATOMIC>(tr, grad_W, j0 + (int64_t)l * NT, m);
+        // batch split over blockIdx.y: every group writes its own partial array (part_stride
+        // elements apart, summed afterwards in a fixed order), or adds atomically into the one array
+        if (ATOMIC && part_stride == 0)
+            lds_to_rows<K, NT, true>(tr, grad_W, j0 + (int64_t)l * NT, m);
+        else
+            lds_to_rows<K, NT, false>(tr, grad_W + (size_t)blockIdx.y * (size_t)part_stride, j0 + (int64_t)l * NT, m);
     }
 }
 
@@ -510,6 +515,21 @@ k_backward_weight_generic(const float* __restrict__ g, const TS* __restrict__ x,
     if (e < N) {
         if (ATOMIC) unsafeAtomicAdd(grad_W + e, acc);
         else grad_W[e] = acc;
+    }
+}
+
+// out[e] = part[0][e] + part[1][e] + ... (n % 4 == 0, 16-byte aligned): the partial weight gradients of
+// a split batch, added in a fixed order.
+__global__ void k_sum_parts(const float* __restrict__ part, int groups, size_t n, float* __restrict__ out) {
+    size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x, nv = n / 4;
+    for (; v < nv; v += step) {
+        float4 a = reinterpret_cast<const float4*>(part)[v];
+        for (int q = 1; q < groups; ++q) {
+            const float4 t = reinterpret_cast<const float4*>(part + (size_t)q * n)[v];
+            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        reinterpret_cast<float4*>(out)[v] = a;
     }
 }
 
@@ -622,20 +642,28 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     if (c->slot_order_for != idx) USL_TRY(usl_build_slot_order(c, idx));
     const uint8_t* perm = c->slot_order;
     dim3 grid((unsigned)nblk, (unsigned)G);
-    if (G > 1) {
-        hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W,
-                           (size_t)c->m * c->k);
+    // a split batch leaves G partial gradients: in scratch, summed afterwards in a fixed order (no
+    // atomics, reproducible), unless that scratch would be out of proportion
+    const size_t N = (size_t)c->m * c->k;
+    int64_t part_stride = 0;
+    float* dst = grad_W;
+    if (G > 1 && (size_t)G * N * 4 <= ((size_t)1 << 29) && N % 4 == 0 && (uintptr_t)grad_W % 16 == 0) {
+        USL_TRY(usl_reserve(c, (void**)&c->gw_part, &c->gw_part_cap, (size_t)G * N * 4));
+        part_stride = (int64_t)N;
+        dst = c->gw_part;
+    } else if (G > 1) {
+        hipLaunchKernelGGL(k_fill_zero, dim3(c->num_cu * 4), dim3(256), 0, c->stream, grad_W, N);
     }
 #define USL_BW(MODE, AT)                                                                                \
     do {                                                                                                \
         if (dense && MODE == 0) {                                                                       \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, false>, lds));             \
             hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, false>), grid, dim3(NT), lds, \
-                               c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);       \
+                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride); \
         } else {                                                                                        \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, true>, lds));              \
             hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, true>), grid, dim3(NT), lds, \
-                               c->stream, g, (const TS*)x, idx, grad_W, c->m, c->d, b, tg, perm);       \
+                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride); \
         }                                                                                               \
     } while (0)
     const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : (tg.buf_stride && LPT > 1 ? 3 : 0));
@@ -644,6 +672,12 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     else if (mode == 2) { if (G > 1) USL_BW(LPT == 1 ? 2 : 0, true); else USL_BW(LPT == 1 ? 2 : 0, false); }
     else { if (G > 1) USL_BW(0, true); else USL_BW(0, false); }
 #undef USL_BW
+    if (part_stride) {
+        USL_TRY(usl_check_launch(c, "backward_weight"));
+        const size_t blocks = (N / 4 + 255) / 256;
+        hipLaunchKernelGGL(k_sum_parts, dim3((unsigned)(blocks < (size_t)c->num_cu * 8 ? blocks : (size_t)c->num_cu * 8)),
+                           dim3(256), 0, c->stream, c->gw_part, G, N, grad_W);
+    }
     return usl_check_launch(c, "backward_weight");
 }
 

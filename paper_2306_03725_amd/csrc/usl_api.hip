@@ -31,7 +31,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
-                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out};
+                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);

@@ -45,6 +45,7 @@ struct usl_ctx {
     void* sub_W;              size_t sub_W_cap;
     float* predict_out;       size_t predict_out_cap;   // [chunk][m] scores of usl_predict, one chunk of instances at a time
     uint64_t* topk_cand;      size_t topk_cand_cap;  // [b][segments][kk] packed (score, label) keys
+    float* gw_part;           size_t gw_part_cap;   // [groups][m*k] partial weight gradients of a split batch
     float* gxT;               size_t gxT_cap;  // [tiles][d][32] input gradient in the same layout
 };
 
