@@ -191,18 +191,27 @@ k_csc_order(const uint32_t* __restrict__ count, int d, uint32_t* __restrict__ or
 
 // Weights in list order, as float32 (refreshed on every call: W changes with every Adam step).  The lists of
 // one label window draw on a contiguous slice of W (window labels * k values); workgroups are dealt round-robin to the 8 XCDs,
-// so window = f(blockIdx % 8) keeps a slice in one XCD's L2 while its GW_BPW workgroups pick it apart.
-constexpr int GW_BPW = 32, GW_NT = 1024;
+// so window = f(blockIdx % 8) keeps a slice in one XCD's L2 while its bpw workgroups pick it apart.
+// bpw workgroups share a window: 32, or 128 when there are so few windows that 32 would leave most of
+// the chip idle and every lane a long chain of dependent loads.
+constexpr int GW_NT = 1024;
 template <typename TS>
 __global__ void __launch_bounds__(GW_NT)
 k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const uint32_t* __restrict__ ptr,
-           int d, int nwin, float* __restrict__ wl) {
-    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int w = (local / GW_BPW) * 8 + xcd;
-    if (w >= nwin) return;
+           int d, int nwin, float* __restrict__ wl, int bpw) {
+    int w, local;
+    if (nwin >= 8) {
+        const int xcd = blockIdx.x & 7;
+        local = blockIdx.x >> 3;
+        w = (local / bpw) * 8 + xcd;
+        if (w >= nwin) return;
+    } else {   // fewer windows than XCDs (W is small then): every window is spread over the whole chip
+        w = (int)(blockIdx.x % (unsigned)nwin);
+        local = (int)(blockIdx.x / (unsigned)nwin);
+    }
     const uint32_t p0 = ptr[(size_t)w * d], p1 = ptr[(size_t)(w + 1) * d];
-    constexpr uint32_t STEP = GW_BPW * GW_NT;
-    uint32_t p = p0 + (local % GW_BPW) * GW_NT + threadIdx.x;
+    const uint32_t STEP = (uint32_t)bpw * GW_NT;
+    uint32_t p = p0 + (local % bpw) * GW_NT + threadIdx.x;
     for (; p + 3 * STEP < p1; p += 4 * STEP) {
         uint32_t e[4];
 #pragma unroll
@@ -485,13 +494,14 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
     for (int q = 0; q < 31; ++q)
         if ((1 << q) == c->k) kshift = q;
     {   // weights in list order
-        const unsigned blocks = (unsigned)((nwin + 7) / 8) * 8 * GW_BPW;
+        const int bpw = nwin >= 8 ? 32 : 128;
+        const unsigned blocks = (unsigned)(nwin >= 8 ? (nwin + 7) / 8 * 8 : nwin) * bpw;
         if (c->storage == USL_F32)
             hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw);
         else
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw);
     }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
