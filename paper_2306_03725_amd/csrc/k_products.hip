@@ -20,11 +20,13 @@ namespace {
 // walk the batch in step, so without this every row is first touched by all of them at once and
 // the whole chip waits out an HBM round trip per row.  Workgroups are dealt to the 8 XCDs round
 // robin; those of one XCD share the row between them, one load per 128-byte line.
+// `share` = workgroups of one XCD that are resident together (the grid may hold several rounds of them):
+// those, consecutive in blockIdx, split the row between them.
 template <typename TS>
-__device__ __forceinline__ void prefetch_row_slice(const TS* __restrict__ row, int n,
+__device__ __forceinline__ void prefetch_row_slice(const TS* __restrict__ row, int n, int share,
                                                    int tid = (int)threadIdx.x) {
     const int lines = (int)(((size_t)n * sizeof(TS) + 127) / 128);
-    const int nsl = max(1, (int)(gridDim.x >> 3));
+    const int nsl = max(1, min((int)(gridDim.x >> 3), share));
     const int sl = (int)(blockIdx.x >> 3) % nsl;
     const int per = (lines + nsl - 1) / nsl;
     const int line = sl * per + tid;
@@ -40,6 +42,7 @@ struct TileGeom {
     int vec_ok;         // 16-byte copies allowed
     int flag_offset;    // byte offset in LDS of the per-wavefront flags of backward_weight
     int buf_stride;     // elements between the two row buffers of MODE 3 (0 = one buffer)
+    int share;          // workgroups resident together on one XCD (they split the warm-up of a row)
 };
 
 // ---------------------------------------------------------------------------- forward
@@ -54,7 +57,9 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
           const uint8_t* __restrict__ perm) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
-    if (MODE == 0 && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
+    if ((MODE == 0 || MODE == 1) && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
+    // sliced float32 rows are exactly two halves of 32768 columns (the fast path stops at d = 65536)
+    constexpr bool HALVES = MODE == 1 && sizeof(TS) == 4 && USL_ROW_LDS_BYTES == 131072;
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
     uint32_t pk[LPT][K / 2];
     float w[LPT][K];
@@ -68,7 +73,7 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
     }
     const int64_t jme = j0 + threadIdx.x;
     // 32 words of zeros (one per bank) behind the slice buffer, for the masked gathers of MODE 1
-    const uint32_t zcol = (uint32_t)tg.part_cols + (uint32_t)(threadIdx.x & 31) * (4 / sizeof(TS));
+    const uint32_t zcol = (uint32_t)tg.part_cols;   // every masked lane reads the same word: one broadcast, one bank
     if (MODE == 1) {
         __syncthreads();
         if (threadIdx.x < 32)
@@ -110,7 +115,7 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
             if (i + 1 < i_end)
                 stage<TS, NT, false>(x + (size_t)(i + 1) * d, lds + (size_t)((i + 1 - i_begin) & 1) * tg.buf_stride, d,
                                      tg.vec_ok);
-            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d);
+            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d, tg.share);
 #pragma unroll
             for (int l = 0; l < LPT; ++l) {
                 if (i > i_begin && jme + (int64_t)l * NT < m)   // spread over the gathers, as in the loop below
@@ -183,7 +188,11 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                 __syncthreads();
                 stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok);
                 __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d);
+                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tg.share);
+                if (HALVES && part > 0) {
+#pragma unroll
+                    for (int l = 0; l < LPT; ++l) flip_half(pk[l]);
+                }
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     // one score of the previous instance leaves between two labels' gathers: four stores
@@ -198,6 +207,8 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                             xv = gather_row0<K>(pk[l], t);
                         } else if (MODE == 0) {
                             xv = lds_val(lds, col_of<K>(pk[l], t));
+                        } else if (HALVES) {
+                            xv = gather_half<K>(pk[l], t, zcol * 4u);
                         } else {
                             // sliced rows: a slot outside the slice reads a word of zeros behind it
                             // (no branch, so the gathers stay pipelined)
@@ -212,6 +223,10 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                     // finish the sum here; left alone the compiler sinks the multiply-adds into
                     // the guarded store and keeps every gathered value alive until then
                     asm volatile("" : "+v"(acc[l]));
+                }
+                if (HALVES && part > 0) {
+#pragma unroll
+                    for (int l = 0; l < LPT; ++l) flip_half(pk[l]);
                 }
             }
 #pragma unroll
@@ -269,7 +284,9 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   int b, TileGeom tg, const uint8_t* __restrict__ perm, int64_t part_stride) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
-    if (MODE == 0 && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
+    if ((MODE == 0 || MODE == 1) && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
+    // sliced float32 rows are exactly two halves of 32768 columns (the fast path stops at d = 65536)
+    constexpr bool HALVES = MODE == 1 && sizeof(TS) == 4 && USL_ROW_LDS_BYTES == 131072;
     const int64_t j0 = (int64_t)blockIdx.x * (NT * LPT);
     uint32_t pk[LPT][K / 2];
     float acc[LPT][K];
@@ -284,7 +301,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
     }
     const int64_t jme = j0 + threadIdx.x;
     // 32 words of zeros (one per bank) behind the slice buffer, for the masked gathers of MODE 1
-    const uint32_t zcol = (uint32_t)tg.part_cols + (uint32_t)(threadIdx.x & 31) * (4 / sizeof(TS));
+    const uint32_t zcol = (uint32_t)tg.part_cols;   // every masked lane reads the same word: one broadcast, one bank
     if (MODE == 1) {
         __syncthreads();
         if (threadIdx.x < 32)
@@ -333,7 +350,7 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 const int64_t j = jme + (int64_t)l * NT;
                 gnext[l] = (j < m && i + 1 < i_end) ? g[(size_t)(i + 1) * m + j] : 0.f;
             }
-            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d);
+            if (i + 2 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 2) * d, d, tg.share);
             const uint32_t* wf = live_flags + ((i - i_begin) & 1) * (NT / 64);
             uint32_t live = 0;
 #pragma unroll
@@ -442,7 +459,11 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                 if (part > 0) __syncthreads();
                 stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok, tid);
                 __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tid);
+                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tg.share, tid);
+                if (HALVES && part > 0) {
+#pragma unroll
+                    for (int l = 0; l < LPT; ++l) flip_half(pk[l]);
+                }
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     if (SKIP && !__any(gv[l] != 0.f)) continue;
@@ -454,6 +475,8 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                             xv = gather_row0<K>(pk[l], t);
                         } else if (MODE == 0) {
                             xv = lds_val(lds, col_of<K>(pk[l], t));
+                        } else if (HALVES) {
+                            xv = gather_half<K>(pk[l], t, zcol * 4u);
                         } else {
                             const uint32_t c = col_of<K>(pk[l], t) - (uint32_t)c0;
                             xv = lds_val(lds, c < cols ? c : zcol);
@@ -461,6 +484,10 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                         acc[l][t] = fmaf(gv[l], xv, acc[l][t]);
                         if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
                     }
+                }
+                if (HALVES && part > 0) {
+#pragma unroll
+                    for (int l = 0; l < LPT; ++l) flip_half(pk[l]);
                 }
             }
         }
@@ -572,6 +599,7 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
                                 : (size_t)tg.part_cols * esize + 128;   // + the zero words
     *lds_bytes = (*lds_bytes + 15) & ~(size_t)15;
     tg.buf_stride = 0;
+    tg.share = 1;
     if (!multi_row && tg.nparts == 1 && 2 * *lds_bytes + 256 <= (size_t)USL_ROW_LDS_BYTES + 8192) {
         tg.buf_stride = (int)(*lds_bytes / esize);   // a second row buffer: copy and gathers overlap
         *lds_bytes *= 2;
@@ -582,6 +610,16 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
 }
 
 inline size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+// Workgroups of nt lanes and lds bytes that one XCD (an eighth of the compute units) holds at a time:
+// per compute unit 160 KB of LDS and 2048 lanes.
+inline int resident_per_xcd(const usl_ctx* c, size_t lds, int nt) {
+    size_t per_cu = (size_t)(160 * 1024) / (lds ? lds : 1);
+    if (per_cu > (size_t)(2048 / nt)) per_cu = (size_t)(2048 / nt);
+    if (per_cu < 1) per_cu = 1;
+    const int cus = c->num_cu / 8 > 0 ? c->num_cu / 8 : 1;
+    return (int)per_cu * cus;
+}
 
 template <typename KERNEL>
 usl_status allow_lds(usl_ctx* c, KERNEL kern, size_t bytes) {
@@ -599,6 +637,7 @@ usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void
     int G;
     TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
     lds = max_sz(lds, (size_t)NT * (K + 1) * 4);  // row tile, or the idx / W transposition buffer
+    tg.share = resident_per_xcd(c, lds, NT);
     if (c->slot_order_for != idx) USL_TRY(usl_build_slot_order(c, idx));
     const uint8_t* perm = c->slot_order;
     dim3 grid((unsigned)nblk, (unsigned)G);
@@ -639,6 +678,7 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     int G;
     TileGeom tg = plan(c, (int)sizeof(TS), b, nblk, x, &lds, &G, LPT == 1);
     lds = max_sz(lds, (size_t)NT * (K + 1) * 4);
+    tg.share = resident_per_xcd(c, lds, NT);
     if (c->slot_order_for != idx) USL_TRY(usl_build_slot_order(c, idx));
     const uint8_t* perm = c->slot_order;
     dim3 grid((unsigned)nblk, (unsigned)G);
@@ -656,9 +696,10 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     }
 #define USL_BW(MODE, AT)                                                                                \
     do {                                                                                                \
-        if (dense && MODE == 0) {                                                                       \
-            USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, false>, lds));             \
-            hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, false>), grid, dim3(NT), lds, \
+        constexpr bool DENSE_OK = (MODE) == 0;   /* the variant without the tests exists for whole rows only */ \
+        if (dense && DENSE_OK) {                                                                        \
+            USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>, lds));         \
+            hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>), grid, dim3(NT), lds, \
                                c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride); \
         } else {                                                                                        \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, true>, lds));              \

@@ -145,6 +145,20 @@ template <int K>
 __device__ __forceinline__ float gather_row0(const uint32_t (&pk)[K / 2], int t) {
     return *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(byte_off4<K>(pk, t)));
 }
+// A float32 row cut into two halves of 32768 columns (the LDS budget): slot t of the half that is staged,
+// or, for a slot of the other half, the lane's word of zeros behind the buffer (zbyte >= 131072 is its LDS
+// address).  While the upper half is staged the packed indices have bit 15 flipped, so "in this half" is
+// "column < 32768" both times and the choice is one unsigned minimum.
+template <int K>
+__device__ __forceinline__ float gather_half(const uint32_t (&pk)[K / 2], int t, uint32_t zbyte) {
+    const uint32_t off = byte_off4<K>(pk, t);
+    return *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(off < zbyte ? off : zbyte));
+}
+template <int N>
+__device__ __forceinline__ void flip_half(uint32_t (&pk)[N]) {
+#pragma unroll
+    for (int q = 0; q < N; ++q) pk[q] ^= 0x80008000u;
+}
 __device__ __forceinline__ bool lds_starts_at_zero(const void* dyn_lds) {
     return (uint32_t)(uintptr_t)((const __attribute__((address_space(3))) void*)dyn_lds) == 0u;
 }
