@@ -8,8 +8,6 @@
 // 16-byte loads, and every gather is an LDS read.  idx and W therefore leave HBM once per
 // workgroup, x is re-read once per label block (it stays in L2 / Infinity Cache), and out /
 // grad_W are written with coalesced stores.
-#include <stdlib.h>
-
 #include "k_products_common.h"
 
 using namespace usl_products;
