@@ -52,37 +52,39 @@ k_topk_segments(const float* __restrict__ out, int64_t m, int kk, int nseg, uint
     __shared__ uint64_t list[TK_MAX * TK_EPT];
     __shared__ uint32_t count;
     const int64_t seg0 = (int64_t)blockIdx.x * TK_SEG;
-    const float* row = out + (int64_t)blockIdx.y * m;
-    // label of register e of this lane
-    auto label_of = [&](int e) -> int64_t {
-        return VEC ? seg0 + ((int64_t)(e >> 2) * TK_NT + threadIdx.x) * 4 + (e & 3)
-                   : seg0 + (int64_t)e * TK_NT + threadIdx.x;
+    const float* row = out + (int64_t)blockIdx.y * m + seg0;
+    const int lim = (int)min((int64_t)TK_SEG, m - seg0);   // labels of this segment that exist
+    const int tid = (int)threadIdx.x;
+    // label of register e of this lane, counted from the segment's first (32-bit arithmetic throughout)
+    auto local_of = [&](int e) -> int {
+        return VEC ? ((e >> 2) * TK_NT + tid) * 4 + (e & 3) : e * TK_NT + tid;
     };
     float v[TK_EPT];
     if (VEC) {
 #pragma unroll
         for (int e = 0; e < TK_EPT; e += 4) {
-            const int64_t j = label_of(e);
-            const float4 q = j < m ? *reinterpret_cast<const float4*>(row + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int j = local_of(e);
+            const float4 q = j < lim ? *reinterpret_cast<const float4*>(row + j) : make_float4(0.f, 0.f, 0.f, 0.f);
             v[e] = q.x; v[e + 1] = q.y; v[e + 2] = q.z; v[e + 3] = q.w;
         }
     } else {
 #pragma unroll
         for (int e = 0; e < TK_EPT; ++e) {
-            const int64_t j = label_of(e);
-            v[e] = j < m ? row[j] : 0.f;
+            const int j = local_of(e);
+            v[e] = j < lim ? row[j] : 0.f;
         }
     }
     // the lane's best score; labels grow with e, so the first of equal scores is the smaller label
     float top = 0.f;
-    int top_e = -1;
+    int top_j = -1;
 #pragma unroll
     for (int e = 0; e < TK_EPT; ++e) {
-        const bool better = label_of(e) < m && (top_e < 0 || v[e] > top);
+        const int j = local_of(e);
+        const bool better = j < lim && (top_j < 0 || v[e] > top);
         top = better ? v[e] : top;
-        top_e = better ? e : top_e;
+        top_j = better ? j : top_j;
     }
-    const uint64_t mine = top_e >= 0 ? score_key(top, (uint32_t)label_of(top_e)) : 0ull;
+    const uint64_t mine = top_j >= 0 ? score_key(top, (uint32_t)(seg0 + top_j)) : 0ull;
     uint64_t tau = ~0ull;
     for (int r = 0; r < kk && tau != 0; ++r) tau = block_max(mine < tau ? mine : 0ull, red);
     if (threadIdx.x == 0) count = 0;
@@ -92,9 +94,9 @@ k_topk_segments(const float* __restrict__ out, int64_t m, int kk, int nseg, uint
     const float tau_score = tau == 0 ? -INFINITY : __uint_as_float((tu & 0x80000000u) ? (tu & 0x7FFFFFFFu) : ~tu);
 #pragma unroll
     for (int e = 0; e < TK_EPT; ++e) {
-        const int64_t j = label_of(e);
-        if (j < m && v[e] >= tau_score) {
-            const uint64_t key = score_key(v[e], (uint32_t)j);
+        const int j = local_of(e);
+        if (j < lim && v[e] >= tau_score) {
+            const uint64_t key = score_key(v[e], (uint32_t)(seg0 + j));
             if (key >= tau) list[atomicAdd(&count, 1u)] = key;
         }
     }
