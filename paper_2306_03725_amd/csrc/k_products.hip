@@ -440,24 +440,29 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
             } else {
                 __syncthreads();
             }
-            {
+            // The next instance's gradients are requested after the row copy, not before it: they come
+            // from HBM, and the copy's wait for its own loads would wait for them as well.
+            auto load_next = [&]() {
                 const float* gr = g + (size_t)(i + 1) * m + j0;
 #pragma unroll
                 for (int l = 0; l < LPT; ++l) {
                     const int jl = tid + l * NT;
                     gnext[l] = (jl < nlab && i + 1 < i_end) ? gr[jl] : 0.f;
                 }
-            }
-            if (!live) continue;
+            };
             const int nparts = MODE == 1 ? tg.nparts : 1;
 #pragma unroll 1
             for (int part = 0; part < nparts; ++part) {
                 const int c0 = part * tg.part_cols;
                 const uint32_t cols = (uint32_t)min(tg.part_cols, d - c0);
-                if (part > 0) __syncthreads();
-                stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok, tid);
-                __syncthreads();
-                if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tg.share, tid);
+                if (live) {   // the same for every lane of the workgroup
+                    if (part > 0) __syncthreads();
+                    stage<TS, NT>(x + (size_t)i * d + c0, lds, (int)cols, tg.vec_ok, tid);
+                    __syncthreads();
+                    if (part == nparts - 1 && i + 1 < i_end) prefetch_row_slice<TS>(x + (size_t)(i + 1) * d, d, tg.share, tid);
+                }
+                if (part == 0) load_next();
+                if (!live) break;
                 if (HALVES && part > 0) {
 #pragma unroll
                     for (int l = 0; l < LPT; ++l) flip_half(pk[l]);
