@@ -348,10 +348,20 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
     constexpr int U = 8;
     if (p < p1) {
         const int sub = threadIdx.x & 7, gl = (threadIdx.x & 63) & ~7;
-        uint32_t pp = min(p + sub, p1 - 1);
-        int32_t jm = label_of(slot[pp]);
-        float wm = p + sub < p1 ? wl[pp] : 0.f;   // a masked entry adds 0*0, whatever the repeated piece holds
-        while (true) {
+        // The (slot, weight) pairs are requested two trips ahead, into two register sets used in turn: they
+        // stream from HBM, and one trip is less than that round trip.
+        auto fetch = [&](uint32_t at, uint32_t& raw, float& wv) {
+            const uint32_t pp = min(at + sub, p1 - 1);
+            raw = slot[pp];
+            wv = at + sub < p1 ? wl[pp] : 0.f;   // a masked entry adds 0*0, whatever the repeated piece holds
+        };
+        uint32_t rawA, rawB = 0;
+        float wA, wB = 0.f;
+        fetch(p, rawA, wA);
+        if (p + U < p1) fetch(p + U, rawB, wB);
+        auto trip = [&](uint32_t& raw, float& wv) -> bool {
+            const int32_t jm = label_of(raw);
+            const float wm = wv;
             int32_t j[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) j[q] = __shfl(jm, gl + q);
@@ -370,20 +380,19 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
             float w[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) w[q] = __shfl(wm, gl + q);
-            const uint32_t pn = p + U;
-            if (pn < p1) {
-                pp = min(pn + sub, p1 - 1);
-                jm = label_of(slot[pp]);
-                wm = pn + sub < p1 ? wl[pp] : 0.f;
-            }
+            if (p + 2 * U < p1) fetch(p + 2 * U, raw, wv);
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const float4 vv = p + q < p1 ? v[q] : make_float4(0.f, 0.f, 0.f, 0.f);
                 acc.x = fmaf(w[q], vv.x, acc.x); acc.y = fmaf(w[q], vv.y, acc.y);
                 acc.z = fmaf(w[q], vv.z, acc.z); acc.w = fmaf(w[q], vv.w, acc.w);
             }
-            if (pn >= p1) break;
-            p = pn;
+            p += U;
+            return p >= p1;
+        };
+        while (true) {
+            if (trip(rawA, wA)) break;
+            if (trip(rawB, wB)) break;
         }
     }
     if (SPLIT > 1) {
