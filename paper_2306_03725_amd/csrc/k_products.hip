@@ -216,7 +216,14 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                         acc[l] = fmaf(w[l][t], xv, acc[l]);
                         // a few gathers in flight at a time: their results would otherwise
                         // crowd out the resident indices and weights
-                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                        if ((t & 7) == 7) {
+                            if (MODE == 0 && sizeof(TS) == 4) {
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                     }
                     // finish the sum here; left alone the compiler sinks the multiply-adds into
                     // the guarded store and keeps every gathered value alive until then
@@ -485,7 +492,14 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                             xv = lds_val(lds, c < cols ? c : zcol);
                         }
                         acc[l][t] = fmaf(gv[l], xv, acc[l][t]);
-                        if ((t & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+                        if ((t & 7) == 7) {
+                            if (MODE == 0 && sizeof(TS) == 4) {   // 8 addresses, 8 reads, 8 multiply-adds
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                     }
                 }
                 if (HALVES && part > 0) {
