@@ -221,6 +221,10 @@ k_forward(const TS* __restrict__ x, const int32_t* __restrict__ idx, const TS* _
                                 __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
                                 __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
                                 __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                            } else if (HALVES) {   // two instructions per address here
+                                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
                             }
                             __builtin_amdgcn_sched_barrier(0);
                         }
@@ -495,6 +499,10 @@ k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                         if ((t & 7) == 7) {
                             if (MODE == 0 && sizeof(TS) == 4) {   // 8 addresses, 8 reads, 8 multiply-adds
                                 __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                            } else if (HALVES) {
+                                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
                                 __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
                                 __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
                             }
