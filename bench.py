@@ -23,7 +23,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # same counters read for a plain copy of known size); summary and commands in
 # profiles/train_step_large_f32_hbm_bytes.txt.  Only the workload it was measured on has an entry.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 5538694 * 1024, "forward": 903344 * 1024, "backward_weight": 918642 * 1024},
+    "large": {"backward_input": 5527399 * 1024, "forward": 903295 * 1024, "backward_weight": 918642 * 1024},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
