@@ -625,7 +625,9 @@ TileGeom plan(const usl_ctx* c, int esize, int b, int64_t nblk, const void* x, s
     *lds_bytes = (*lds_bytes + 15) & ~(size_t)15;
     tg.buf_stride = 0;
     tg.share = 1;
-    if (!multi_row && tg.nparts == 1 && 2 * *lds_bytes + 256 <= (size_t)USL_ROW_LDS_BYTES + 8192) {
+    // bfloat16 rows in two buffers are gathered through byte offsets held in 16 bits: at most 32768 columns
+    const bool offsets_fit = esize == 4 || c->d <= 32768;
+    if (!multi_row && tg.nparts == 1 && offsets_fit && 2 * *lds_bytes + 256 <= (size_t)USL_ROW_LDS_BYTES + 8192) {
         tg.buf_stride = (int)(*lds_bytes / esize);   // a second row buffer: copy and gathers overlap
         *lds_bytes *= 2;
     }
@@ -654,6 +656,20 @@ usl_status allow_lds(usl_ctx* c, KERNEL kern, size_t bytes) {
     return USL_OK;
 }
 
+// The float32 whole-row and half-row gathers use the column's byte offset as the LDS address: the
+// kernel's dynamic LDS must start at address 0, which holds exactly when the kernel has no static LDS.
+// That is a property of the compiled kernel, so it is checked here, once per kernel, before the launch:
+// a kernel that lost it is refused with an error instead of leaving its output unwritten.
+template <typename KERNEL>
+usl_status require_lds_at_zero(usl_ctx* c, KERNEL kern, const char* what) {
+    hipFuncAttributes fa;
+    USL_HIP(c, hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)));
+    if (fa.sharedSizeBytes != 0)
+        USL_FAIL(c, USL_EUNSUPPORTED, "%s: the kernel has %zu bytes of static LDS, its row buffer does not start at LDS address 0",
+                 what, (size_t)fa.sharedSizeBytes);
+    return USL_OK;
+}
+
 template <int K, int LPT, int NT, typename TS>
 usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void* W, float* out,
                        int b) {
@@ -669,6 +685,11 @@ usl_status run_forward(usl_ctx* c, const void* x, const int32_t* idx, const void
 #define USL_FW(MODE)                                                                        \
     do {                                                                                    \
         USL_TRY(allow_lds(c, k_forward<K, LPT, NT, TS, MODE>, lds));                        \
+        if (((MODE) == 0 || (MODE) == 1) && sizeof(TS) == 4) {                              \
+            static bool checked = false;                                                    \
+            if (!checked) USL_TRY(require_lds_at_zero(c, k_forward<K, LPT, NT, TS, MODE>, "forward")); \
+            checked = true;                                                                 \
+        }                                                                                   \
         hipLaunchKernelGGL((k_forward<K, LPT, NT, TS, MODE>), grid, dim3(NT), lds, c->stream, \
                            (const TS*)x, idx, (const TS*)W, out, c->m, c->d, b, tg, perm);  \
     } while (0)
@@ -722,6 +743,14 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
 #define USL_BW(MODE, AT)                                                                                \
     do {                                                                                                \
         constexpr bool DENSE_OK = (MODE) == 0;   /* the variant without the tests exists for whole rows only */ \
+        if (((MODE) == 0 || (MODE) == 1) && sizeof(TS) == 4) {                                          \
+            static bool checked = false;                                                                \
+            if (!checked) {                                                                             \
+                USL_TRY(require_lds_at_zero(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, true>, "backward_weight")); \
+                if (DENSE_OK) USL_TRY(require_lds_at_zero(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>, "backward_weight")); \
+            }                                                                                           \
+            checked = true;                                                                             \
+        }                                                                                               \
         if (dense && DENSE_OK) {                                                                        \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>, lds));         \
             hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>), grid, dim3(NT), lds, \

@@ -25,6 +25,8 @@ SHAPES = {
     "sliced_small": (2000, 40000, 16, 3),
     "wide_d": (1000, 70000, 8, 2),             # d > 65536: indices do not fit 16 bits
     "one": (1, 1, 1, 1),
+    "bf16_past_16bit_offsets": (263000, 33000, 32, 2),   # bfloat16 rows whose byte offsets exceed 16 bits
+    "bf16_two_rows_would_fit": (263000, 34752, 32, 3),   # ... at the largest d whose two rows would still fit LDS
 }
 
 
@@ -47,7 +49,9 @@ def gu():
     return gpu_util
 
 
-CASES = [(n, "f32") for n in SHAPES] + [(n, "bf16") for n in ("tiny", "ragged_small", "k5", "k64", "big_blocks", "sliced_small")]
+CASES = [(n, "f32") for n in SHAPES if not n.startswith("bf16_")] + \
+        [(n, "bf16") for n in ("tiny", "ragged_small", "k5", "k64", "big_blocks", "sliced_small",
+                               "bf16_past_16bit_offsets", "bf16_two_rows_would_fit")]
 
 
 @pytest.mark.parametrize("name,storage", CASES)
