@@ -75,6 +75,136 @@ def cpu_baseline(cfg, budget_s=12.0, max_reps=5):
                       "%.2f s per step" % (len(times), cfg.b, per_step)}
 
 
+class Bench:
+    """Resident state and inputs of one workload, and the two ways of running a step."""
+
+    def __init__(self, cfg, torch, usl, wl):
+        self.cfg, self.torch, self.wl = cfg, torch, wl
+        m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+        dev = torch.device("cuda:0")
+        self.stream = torch.cuda.current_stream()
+        self.L = usl.Layer(m, d, k, b, cfg.storage, self.stream.cuda_stream)
+
+        def up(a):
+            a = np.ascontiguousarray(a)
+            if a.dtype == np.uint16:
+                a = a.view(np.int16)
+            return torch.from_numpy(a).to(dev)
+
+        self.idx = torch.empty((m, k), dtype=torch.int32, device=dev)
+        self.L.init_indices(self.idx, 1000 * cfg.index + wl.STREAM_IDX)
+        self.W = up(wl.gen_W(cfg))
+        self.m1 = torch.zeros((m, k), dtype=torch.float32, device=dev)
+        self.m2 = torch.zeros((m, k), dtype=torch.float32, device=dev)
+        self.gW = torch.empty((m, k), dtype=torch.float32, device=dev)
+        self.xs = [up(wl.gen_x(cfg, i)) for i in range(cfg.n_x_batches)]
+        self.tg = [tuple(up(a) for a in wl.gen_targets(cfg, i)) for i in range(cfg.n_x_batches)]
+        self.out = torch.empty((b, m), dtype=torch.float32, device=dev)     # g is written in place
+        self.gx = torch.empty((b, d), dtype=torch.float32, device=dev)
+        self.loss = torch.empty((1,), dtype=torch.float32, device=dev)
+        self.seed = wl.redistribution_seed(cfg)
+        self.scale = float(np.float32(1.0 / b))
+        self.t = 0
+        self.epoch = 0
+
+    def _redistribute(self):
+        cfg = self.cfg
+        if self.wl.is_redistribution_step(cfg, self.t):
+            self.L.redistribute(self.idx, self.W, self.m1, self.m2, cfg.fraction, self.seed, self.epoch)
+            self.epoch += 1
+            return True
+        return False
+
+    def step(self, ev=None):
+        """The step as five separate calls, with an event between the calls when ev is a list."""
+        hp, b, L = self.wl.ADAM, self.cfg.b, self.L
+        self.t += 1
+        x = self.xs[self.t % len(self.xs)]
+        off, lab = self.tg[self.t % len(self.tg)]
+        marks = []
+
+        def mark():
+            if ev is not None:
+                e = self.torch.cuda.Event(enable_timing=True)
+                e.record(self.stream)
+                marks.append(e)
+        mark()
+        L.forward(x, self.idx, self.W, self.out, b); mark()
+        L.bce_loss_grad(self.out, off, lab, self.scale, self.out, self.loss, b); mark()
+        L.backward_weight(self.out, x, self.idx, self.gW, b); mark()
+        L.backward_input(self.out, self.idx, self.W, self.gx, b); mark()
+        L.adam_step(self.W, self.gW, self.m1, self.m2, self.t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"]); mark()
+        if self._redistribute():
+            mark()
+        if ev is not None:
+            ev.append(marks)
+
+    def fused_step(self):
+        hp, b = self.wl.ADAM, self.cfg.b
+        self.t += 1
+        x = self.xs[self.t % len(self.xs)]
+        off, lab = self.tg[self.t % len(self.tg)]
+        self.L.train_step(x, self.idx, self.W, self.m1, self.m2, off, lab, 0, self.scale, self.t, hp["lr"], hp["beta1"],
+                          hp["beta2"], hp["eps"], self.out, self.gW, self.gx, self.loss, b)
+        self._redistribute()
+
+    def timed(self, fn, n):
+        """HIP-event time of n calls of fn on the launch stream, in ms per call."""
+        e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        for _ in range(n):
+            fn()
+        e1.record(self.stream)
+        self.torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    def close(self):
+        self.L.close()
+        for name in list(vars(self)):
+            if name not in ("cfg", "torch", "wl", "t", "epoch"):
+                setattr(self, name, None)
+        self.torch.cuda.empty_cache()
+
+
+CALLS = ["forward", "bce", "backward_weight", "backward_input", "adam", "redistribute"]
+
+
+def per_call_breakdown(B, steps):
+    """The same steps as separate calls with an event between the calls: ms per call and per step."""
+    events = []
+    B.step()
+    sep = B.timed(lambda: B.step(events), steps)
+    per_call = {c: [] for c in CALLS}
+    for marks in events:
+        for i in range(len(marks) - 1):
+            per_call[CALLS[i]].append(marks[i].elapsed_time(marks[i + 1]))
+    return {c: (float(np.mean(v)) if v else None) for c, v in per_call.items()}, sep
+
+
+def workload_summary(name, steps, warmup, torch, usl, wl):
+    """One of the other configurations, reported like the headline one (shorter)."""
+    cfg = wl.CONFIGS[name]
+    B = Bench(cfg, torch, usl, wl)
+    for _ in range(warmup):
+        B.fused_step()
+    torch.cuda.synchronize()
+    ms = B.timed(B.fused_step, steps)
+    call_ms, sep = per_call_breakdown(B, max(2, steps // 2))
+    ab = algorithmic_bytes(cfg)
+    res = {"config": "m=%d d=%d k=%d b=%d %s, redistribution of %.0f%% every %d steps"
+                     % (cfg.m, cfg.d, cfg.k, cfg.b, cfg.storage, 100 * cfg.fraction, cfg.period),
+           "steps": steps, "ms_per_step": round(ms, 4), "steps_per_s": round(1e3 / ms, 2),
+           "algorithmic_GB_per_step": round(ab["step"] / 1e9, 4),
+           "achieved_hbm_GBps": round(ab["step"] / (ms * 1e-3) / 1e9, 1),
+           "hbm_frac_of_peak": round(ab["step"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "separate_calls_ms_per_step": round(sep, 4),
+           "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
+           "call_frac_of_peak": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) for c in CALLS[:5]},
+           "bad_rows": B.L.validate_indices(B.idx), "redistributions": B.epoch}
+    B.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,7 +215,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the squared-hinge sweep and the prediction timing that a default run at N=1 appends")
+                    help="skip the legs a default run at N=1 appends: ceilings, the other workloads, the "
+                         "squared-hinge sweep and the prediction timing")
     ap.add_argument("--sqh-sweep", action="store_true",
                     help="also time the squared-hinge loss and the two backward calls on gradients with "
                          "0 / 90 / 99 / 99.9 %% exact zeros (implicit negative mining, Section 3.3)")
@@ -93,11 +224,16 @@ def main():
                     help="time the step as five separate calls instead of usl_train_step")
     ap.add_argument("--predict", action="store_true",
                     help="also time prediction (Section 2): top-5 labels of every score row and the P@k hit counts")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also run the library's measurement kernels (HBM streams, LDS gathers, L2 to LDS row "
+                         "copies, L2 piece gathers) and relate the step to them")
+    ap.add_argument("--other-workloads", action="store_true",
+                    help="also report the configurations the headline is not quoted on (medium, large_wide, stress)")
     ap.add_argument("--traffic-kib", type=float, default=None,
                     help="HBM KiB per launch of the dominant kernel from rocprofv3 --pmc (FETCH+WRITE, scaled)")
     args = ap.parse_args()
     if not args.no_extras and not args.no_cpu_baseline and args.workload == "large":
-        args.sqh_sweep = args.predict = True     # the default run also reports the widened rows
+        args.sqh_sweep = args.predict = args.ceilings = args.other_workloads = True
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -113,70 +249,11 @@ def main():
     cfg = wl.CONFIGS[args.workload]
     m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
     dev = torch.device("cuda:0")
-    stream = torch.cuda.current_stream()
-    L = usl.Layer(m, d, k, b, cfg.storage, stream.cuda_stream)
+    B = Bench(cfg, torch, usl, wl)
+    L, stream = B.L, B.stream
+    idx, W, gW, gx, out, loss, xs, tg, scale = B.idx, B.W, B.gW, B.gx, B.out, B.loss, B.xs, B.tg, B.scale
 
-    def up(a):
-        a = np.ascontiguousarray(a)
-        if a.dtype == np.uint16:
-            a = a.view(np.int16)
-        return torch.from_numpy(a).to(dev)
-
-    # ---- resident state and inputs
-    idx = torch.empty((m, k), dtype=torch.int32, device=dev)
-    L.init_indices(idx, 1000 * cfg.index + wl.STREAM_IDX)
-    W = up(wl.gen_W(cfg))
-    m1 = torch.zeros((m, k), dtype=torch.float32, device=dev)
-    m2 = torch.zeros((m, k), dtype=torch.float32, device=dev)
-    gW = torch.empty((m, k), dtype=torch.float32, device=dev)
-    xs = [up(wl.gen_x(cfg, i)) for i in range(cfg.n_x_batches)]
-    tg = [tuple(up(a) for a in wl.gen_targets(cfg, i)) for i in range(cfg.n_x_batches)]
-    out = torch.empty((b, m), dtype=torch.float32, device=dev)     # g is written in place
-    gx = torch.empty((b, d), dtype=torch.float32, device=dev)
-    loss = torch.empty((1,), dtype=torch.float32, device=dev)
-    seed = wl.redistribution_seed(cfg)
-    scale = float(np.float32(1.0 / b))
-    hp = wl.ADAM
-    state = {"t": 0, "epoch": 0}
-    calls = ["forward", "bce", "backward_weight", "backward_input", "adam", "redistribute"]
-
-    def step(ev=None):
-        state["t"] += 1
-        t = state["t"]
-        x = xs[t % len(xs)]
-        off, lab = tg[t % len(tg)]
-        marks = []
-
-        def mark():
-            if ev is not None:
-                e = torch.cuda.Event(enable_timing=True)
-                e.record(stream)
-                marks.append(e)
-        mark()
-        L.forward(x, idx, W, out, b); mark()
-        L.bce_loss_grad(out, off, lab, scale, out, loss, b); mark()
-        L.backward_weight(out, x, idx, gW, b); mark()
-        L.backward_input(out, idx, W, gx, b); mark()
-        L.adam_step(W, gW, m1, m2, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"]); mark()
-        if wl.is_redistribution_step(cfg, t):
-            L.redistribute(idx, W, m1, m2, cfg.fraction, seed, state["epoch"])
-            state["epoch"] += 1
-            mark()
-        if ev is not None:
-            ev.append(marks)
-
-    def fused_step():
-        state["t"] += 1
-        t = state["t"]
-        x = xs[t % len(xs)]
-        off, lab = tg[t % len(tg)]
-        L.train_step(x, idx, W, m1, m2, off, lab, 0, scale, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
-                     out, gW, gx, loss, b)
-        if wl.is_redistribution_step(cfg, t):
-            L.redistribute(idx, W, m1, m2, cfg.fraction, seed, state["epoch"])
-            state["epoch"] += 1
-
-    timed_step = step if args.separate_calls else fused_step
+    timed_step = B.step if args.separate_calls else B.fused_step
     for _ in range(args.warmup):
         timed_step()
     torch.cuda.synchronize()
@@ -188,35 +265,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     # ---- the timed region: exactly args.steps steps
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(args.steps):
-        timed_step()
-    e1.record(stream)
-    torch.cuda.synchronize()
+    ms_per_step = B.timed(timed_step, args.steps)
     wall_ms = (time.perf_counter() - t_wall0) * 1e3
-    total_ms = e0.elapsed_time(e1)
     loss_value = float(loss.item())
-    # ---- the same steps as separate calls with an event between the calls: the per-call breakdown
-    events = []
-    step()
-    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    s0.record(stream)
-    for _ in range(args.steps):
-        step(events)
-    s1.record(stream)
-    torch.cuda.synchronize()
-    separate_ms = s0.elapsed_time(s1) / args.steps
+    call_ms, separate_ms = per_call_breakdown(B, args.steps)
     n_bad = L.validate_indices(idx)
-
-    per_call = {c: [] for c in calls}
-    for marks in events:
-        for i in range(len(marks) - 1):
-            per_call[calls[i]].append(marks[i].elapsed_time(marks[i + 1]))
-    call_ms = {c: (float(np.mean(v)) if v else None) for c, v in per_call.items()}
+    calls = CALLS
     ab = algorithmic_bytes(cfg)
-    ms_per_step = total_ms / args.steps
     steps_per_s = 1e3 / ms_per_step
     # the dominant call and its roofline position (algorithmic bytes / measured time)
     dom = max((c for c in calls[:5]), key=lambda c: call_ms[c] or 0.0)
@@ -249,9 +305,33 @@ def main():
                        "usl_adam_step" if args.separate_calls else "usl_train_step (the same five stages in one call)")
                       + ", usl_redistribute on its schedule",
         "separate_calls_ms_per_step": round(separate_ms, 4),
-        "loss": loss_value, "bad_rows": n_bad, "redistributions": state["epoch"],
+        "loss": loss_value, "bad_rows": n_bad, "redistributions": B.epoch,
         "roofline": roof,
     }
+    if args.ceilings:
+        try:
+            from paper_2306_03725_amd import ceilings
+            c = ceilings.run()
+            cu, ghz = c["compute_units"], c["clock_GHz"]
+            gathers = 3.0 * b * m * k                       # one LDS gather per (instance, connection) and product
+            gather_rate = c["lds_gather_b32_conflict_free_lanes_per_clk_cu"] * cu * ghz * 1e9
+            es = 2 if cfg.storage == "bf16" else 4
+            # every product stages its rows into the LDS of every workgroup: per product, label (or feature)
+            # blocks of 2048 x batch rows x row bytes
+            copy_bytes = 3.0 * (-(-m // 2048)) * b * d * es
+            t_gather = gathers / gather_rate * 1e3
+            t_copy = copy_bytes / (c["l2_to_lds_row_copy_aggregate_GBps"] * 1e9) * 1e3
+            t_hbm = ab["step"] / (c["hbm_copy_GBps_read_plus_write"] * 1e9) * 1e3
+            res["ceilings"] = {k_: round(v, 3) for k_, v in c.items()}
+            roof["gather_frac"] = round(t_gather / ms_per_step, 4)
+            roof["gather_note"] = ("3*b*m*k LDS gathers per step at the measured conflict-free ds_read_b32 rate "
+                                   "would take %.3f ms; staging the rows those gathers read, at the measured L2 to "
+                                   "LDS copy rate, %.3f ms; the step's algorithmic HBM bytes at the measured copy "
+                                   "rate, %.3f ms; these three do not overlap inside a product kernel"
+                                   % (t_gather, t_copy, t_hbm))
+            roof["measured_ceilings_frac"] = round((t_gather + t_copy + t_hbm) / ms_per_step, 4)
+        except Exception as exc:   # the headline line must survive a failure of an appended leg
+            res["ceilings"] = {"error": repr(exc)}
     if args.sqh_sweep:
         try:
             # Synthetic stand-in for the gradient of a trained model under the squared hinge loss: the
@@ -320,6 +400,18 @@ def main():
                               "hits": hits.tolist()}
         except Exception as exc:   # the headline line must survive a failure of an appended leg
             res['predict'] = {"error": repr(exc)}
+    B.close()
+    del L, idx, W, gW, gx, out, loss, xs, tg
+    torch.cuda.empty_cache()
+    if args.other_workloads:
+        res["workloads"] = {}
+        for name, steps in (("medium", 50), ("large_wide", 10), ("stress", 4)):
+            if name == cfg.name:
+                continue
+            try:
+                res["workloads"][name] = workload_summary(name, steps, 2, torch, usl, wl)
+            except Exception as exc:   # the headline line must survive a failure of an appended leg
+                res["workloads"][name] = {"error": repr(exc)}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))

@@ -90,6 +90,18 @@ usl_status usl_bce_loss_grad(usl_ctx* ctx, const float* out, const int64_t* tgt_
                              const int32_t* tgt_lab, float scale, float* g, float* loss,
                              int32_t b);
 
+/* usl_bce_loss_grad for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and bit-identical results,
+ * but the per-block loss sums live in a static 1 MiB device array of the library instead of scratch that
+ * the library allocates, and the call itself allocates and frees nothing (the context's first call on a
+ * device, of any kind, reads the device properties and looks the array up).
+ * Limit: ceil(m / 4096) * b <= 131072, else USL_ESHAPE and nothing is launched.
+ * All contexts on one GPU share that GPU's array: two such calls that overlap in time on one GPU (different
+ * streams) race; calls on one stream are ordered and safe.  Every call overwrites the slots it reads. */
+usl_status usl_bce_loss_grad_noalloc(usl_ctx* ctx, const float* out, const int64_t* tgt_off,
+                                     const int32_t* tgt_lab, float scale, float* g, float* loss,
+                                     int32_t b);
+
 /* One-vs-all squared hinge loss, the paper's main loss (Section 3.3), on the same sparse targets:
  *   s[i][j] = +1 iff j is listed for instance i, else -1
  *   loss = scale * sum_ij max(0, 1 - s*z)^2,   g[i][j] = scale * (-2 * s * max(0, 1 - s*z))

@@ -6,6 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libusl.so")
+LIB_CEILINGS = os.path.join(HERE, "libusl_ceilings.so")   # measurement kernels, not part of the training path
 SOURCES = ["usl_api.hip", "k_products.hip", "k_elementwise.hip", "k_backward_input.hip",
            "k_redistribute.hip", "k_schedule.hip", "k_predict.hip"]
 # -packed-fp32-ops: packed FP32 VALU instructions are switched off (they have produced wrong
@@ -44,6 +45,9 @@ def build(force=True, verbose=False):
             sys.stderr.write(out)
             raise RuntimeError("hipcc failed on %s" % src)
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    csrc = os.path.join(CSRC, "ceilings.hip")
+    if force or not os.path.exists(LIB_CEILINGS) or os.path.getmtime(LIB_CEILINGS) < os.path.getmtime(csrc):
+        subprocess.check_call([_hipcc()] + FLAGS + ["-shared", csrc, "-o", LIB_CEILINGS])
     return LIB
 
 

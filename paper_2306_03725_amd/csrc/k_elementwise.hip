@@ -291,6 +291,47 @@ usl_status usl_launch_loss(usl_ctx* c, int loss_kind, const float* out, const in
     return usl_check_launch(c, "loss_finish");
 }
 
+// ---- the loss for callers that cannot allocate: same kernels, per-block sums in a static device array
+// (each GPU the library runs on holds its own copy of the array, at its own address, until the process ends)
+constexpr size_t NOALLOC_SLOTS = 131072;   // 1 MiB of doubles: one per (block of 4096 labels, instance)
+static __device__ __align__(256) double scratch[NOALLOC_SLOTS];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static double* scratch_ptr[NOALLOC_MAX_DEVICES];   // device address of `scratch` on each device, set once
+
+
+// Called once per context when it first touches its device (that device is current): looks up where this
+// device holds the array.  In host code the array's name is only a handle for this lookup.
+usl_status usl_noalloc_setup(usl_ctx* c) {
+    if (c->device < 0 || c->device >= NOALLOC_MAX_DEVICES) return USL_OK;   // the no-alloc call will refuse
+    if (scratch_ptr[c->device]) return USL_OK;
+    double* p = nullptr;
+    USL_HIP(c, hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    scratch_ptr[c->device] = p;
+    return USL_OK;
+}
+
+usl_status usl_launch_loss_noalloc(usl_ctx* c, int loss_kind, const float* out, const int64_t* tgt_off,
+                                   const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b) {
+    const int64_t nchunk = (c->m + BCE_CHUNK - 1) / BCE_CHUNK;
+    const size_t nblk = (size_t)nchunk * b;
+    if (nblk > NOALLOC_SLOTS)
+        USL_FAIL(c, USL_ESHAPE, "ceil(m / %d) * b = %zu per-block sums exceed the %zu the static scratch holds",
+                 BCE_CHUNK, nblk, NOALLOC_SLOTS);
+    double* partials = (c->device >= 0 && c->device < NOALLOC_MAX_DEVICES) ? scratch_ptr[c->device] : nullptr;
+    if (!partials) USL_FAIL(c, USL_EUNSUPPORTED, "no static scratch on device %d", c->device);
+    const bool vec = (c->m % 4 == 0) && ((uintptr_t)out % 16 == 0) && ((uintptr_t)g % 16 == 0);
+    dim3 grid((unsigned)nchunk, (unsigned)b);
+#define USL_LOSS(VEC, KIND)                                                                          \
+    hipLaunchKernelGGL((k_bce<VEC, KIND>), grid, dim3(BCE_NT), 0, c->stream, out, tgt_off, tgt_lab,  \
+                       scale, g, partials, c->m)
+    if (loss_kind == LOSS_BCE) { if (vec) USL_LOSS(true, LOSS_BCE); else USL_LOSS(false, LOSS_BCE); }
+    else                       { if (vec) USL_LOSS(true, LOSS_SQH); else USL_LOSS(false, LOSS_SQH); }
+#undef USL_LOSS
+    USL_TRY(usl_check_launch(c, "loss (static scratch)"));
+    hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, partials, nblk, scale, loss);
+    return usl_check_launch(c, "loss_finish (static scratch)");
+}
+
 usl_status usl_launch_loss_tiles(usl_ctx* c, int loss_kind, float* zg, const int64_t* tgt_off,
                                  const int32_t* tgt_lab, float scale, float* loss, int32_t b,
                                  uint64_t* sampled_labels) {

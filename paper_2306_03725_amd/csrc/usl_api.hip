@@ -69,7 +69,7 @@ usl_status usl_prepare_device(usl_ctx* c) {
                  (size_t)p.sharedMemPerBlock, USL_ROW_LDS_BYTES + 1024);
     c->num_cu = p.multiProcessorCount;
     c->device = dev;
-    return USL_OK;
+    return usl_noalloc_setup(c);   // where this device holds the static scratch of the no-allocation call
 }
 
 usl_status usl_reserve(usl_ctx* c, void** buf, size_t* cap, size_t bytes) {
@@ -133,6 +133,17 @@ extern "C" usl_status usl_bce_loss_grad(usl_ctx* c, const float* out, const int6
     USL_TRY(check_batch(c, b));
     USL_TRY(usl_prepare_device(c));
     return usl_launch_loss(c, 0, out, tgt_off, tgt_lab, scale, g, loss, b);
+}
+
+extern "C" usl_status usl_bce_loss_grad_noalloc(usl_ctx* c, const float* out, const int64_t* tgt_off,
+                                                const int32_t* tgt_lab, float scale, float* g, float* loss,
+                                                int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(out); NEED(tgt_off); NEED(tgt_lab); NEED(g); NEED(loss);
+    if (!(scale == scale) || isinf(scale)) USL_FAIL(c, USL_EINVAL, "scale is not finite");
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    return usl_launch_loss_noalloc(c, 0, out, tgt_off, tgt_lab, scale, g, loss, b);
 }
 
 extern "C" usl_status usl_sqh_loss_grad(usl_ctx* c, const float* out, const int64_t* tgt_off,

@@ -97,6 +97,10 @@ usl_status usl_launch_loss_tiles(usl_ctx* ctx, int loss_kind, float* zg, const i
 // loss_kind: 0 = binary cross-entropy, 1 = squared hinge
 usl_status usl_launch_loss(usl_ctx* ctx, int loss_kind, const float* out, const int64_t* tgt_off,
                            const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
+// the same loss through the static scratch array (no allocation); usl_noalloc_setup runs once per device
+usl_status usl_noalloc_setup(usl_ctx* ctx);
+usl_status usl_launch_loss_noalloc(usl_ctx* ctx, int loss_kind, const float* out, const int64_t* tgt_off,
+                                   const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
 usl_status usl_launch_adam(usl_ctx* ctx, void* W, const float* grad_W, float* m1, float* m2,
                            float lr, float beta1, float beta2, float eps, float inv_c1,
                            float inv_c2);

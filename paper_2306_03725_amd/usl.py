@@ -15,7 +15,7 @@ USL_F32, USL_BF16 = 0, 1
 STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", "USL_EUNSUPPORTED"]
 
 # every symbol include/usl.h declares
-SYMBOLS = ["usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
+SYMBOLS = ["usl_bce_loss_grad_noalloc", "usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
            "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows", "usl_predict",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
@@ -39,6 +39,7 @@ _sig = {
     "usl_forward": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_sqh_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
+    "usl_bce_loss_grad_noalloc": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
     "usl_topk": [_vp, _vp, _i32, _i32, _vp, _vp],
     "usl_predict": [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp],
     "usl_train_step": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _i64, _f32, _f32, _f32, _f32,
@@ -124,6 +125,10 @@ class Layer:
     def bce_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
         self._ck(_lib.usl_bce_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
                                         _ptr(g), _ptr(loss), b))
+
+    def bce_loss_grad_noalloc(self, out, tgt_off, tgt_lab, scale, g, loss, b):
+        self._ck(_lib.usl_bce_loss_grad_noalloc(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,
+                                                _ptr(g), _ptr(loss), b))
 
     def sqh_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
         self._ck(_lib.usl_sqh_loss_grad(self._h, _ptr(out), _ptr(tgt_off), _ptr(tgt_lab), scale,

@@ -12,6 +12,30 @@ from helpers import assert_close
 pytestmark = pytest.mark.gpu
 
 
+def oracle_loss_in_chunks(loss_fn, d_scores, off, lab, scale, rows=32):
+    """The loss of all b x m scores held on the GPU, by the oracle: the loss is a sum over instances, so the
+    scores come to the host a block of instances at a time and the doubles are added up."""
+    import gpu_util as gu
+    b = d_scores.shape[0]
+    total = 0.0
+    for i0 in range(0, b, rows):
+        i1 = min(b, i0 + rows)
+        sub_off = (off[i0:i1 + 1] - off[i0]).astype(np.int64)
+        sub_lab = np.ascontiguousarray(lab[off[i0]:off[i1]])
+        part, _ = loss_fn(gu.host(d_scores[i0:i1]), sub_off, sub_lab if sub_lab.size else np.zeros(1, np.int32), scale)
+        total += part
+    return total
+
+
+def assert_bf16_adam(got_bits, pre):
+    """Stored bfloat16 weight against the oracle's unrounded float32 value: half a bfloat16 unit in the last
+    place (the rounding itself) plus the float tolerance of the Adam state, 1e-4 * (|r| + rms)."""
+    got = wl.bf16_bits_to_f32(got_bits).astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(pre), 1e-30))) - 7)
+    rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))
+    assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre) + 1e-4 * rms).all()
+
+
 def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
     import gpu_util as gu
     from paper_2306_03725_amd import usl
@@ -44,6 +68,7 @@ def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
     print("forward ok", flush=True)
     # BCE in place
     h_out = gu.host(out) if full_loss else None
+    ref_loss_chunks = None if full_loss else oracle_loss_in_chunks(orc.bce_loss_grad, out, off, lab, scale)
     L.bce_loss_grad(out, gu.dev(off), gu.dev(lab), scale, out, loss, b)
     sub_off = np.zeros(n_inst + 1, np.int64)
     sub_lab = []
@@ -61,7 +86,7 @@ def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
         del ref_g, h_out
     else:
         g_J = gu.host(out.index_select(1, dJ).contiguous())
-        assert np.isfinite(loss.item())
+        assert abs(loss.item() - ref_loss_chunks) <= 1e-5 * abs(ref_loss_chunks)
     print("bce ok", flush=True)
     # backward products on the GPU's own g
     gW, gx = gu.empty((m, k)), gu.empty((b, d))
@@ -84,10 +109,7 @@ def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
         if cfg.storage == "f32":
             assert_close(got, W_J, 1e-4, "W")
         else:
-            got = wl.bf16_bits_to_f32(got).astype(np.float64)
-            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(pre), 1e-30))) - 7)
-            rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))   # same guard as assert_close
-            assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre) + 1e-4 * rms).all()
+            assert_bf16_adam(got, pre)
     print("adam ok", flush=True)
     # redistribution, in full
     h_idx, h_W, h_m1, h_m2 = (gu.host(t).copy() for t in (d_idx, d_W, d_m1, d_m2))
@@ -205,14 +227,13 @@ def run_full_train_step(cfg, orc, loss_kind, n_lab=4096, n_inst=4):
     if cfg.storage == "f32":
         assert_close(got, W_J, 1e-4, "W")
     else:
-        got = wl.bf16_bits_to_f32(got).astype(np.float64)
-        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(pre), 1e-30))) - 7)
-        rms = float(np.sqrt(np.mean(pre.astype(np.float64) ** 2)))
-        assert (np.abs(got - pre) <= 0.5 * ulp * (1 + 1e-3) + 1e-4 * np.abs(pre) + 1e-4 * rms).all()
+        assert_bf16_adam(got, pre)
     # the loss value: the separate loss call on scores from the separate forward call is checked in full
     # against the oracle elsewhere; the fused value must agree with it to the order of its additions
     out2 = gu.empty((b, m))
     L.forward(d_x, d_idx, gu.dev(W), out2, b)
+    ref_loss = oracle_loss_in_chunks(loss_fn, out2, off, lab, scale)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
     loss2 = gu.empty((1,))
     (L.bce_loss_grad if loss_kind == 0 else L.sqh_loss_grad)(out2, gu.dev(off), gu.dev(lab), scale, out2, loss2, b)
     assert abs(loss.item() - loss2.item()) <= 1e-5 * abs(loss2.item())
@@ -236,3 +257,142 @@ def test_large_wide_train_step_full_size(orc):
 
 def test_stress_train_step_full_size(orc):
     run_full_train_step(wl.CONFIGS["stress"], orc, 0, n_lab=1024, n_inst=2)
+
+
+class FullSchedule:
+    """The config's own schedule at full size through usl_train_step, as bench.py runs it, with a
+    redistribution after every cfg.period-th step.  Teacher-forced: at a checked step every stage is compared on
+    sampled outputs with the oracle fed the GPU's state before the step; every redistribution is compared in
+    full, bit for bit (from the second one on the layer holds regrown weights: zeros and values of the size of
+    one Adam step, so the magnitude order is full of ties)."""
+
+    def __init__(self, cfg, orc, n_lab=2048, n_inst=2):
+        import gpu_util as gu
+        from paper_2306_03725_amd import usl
+        self.cfg, self.orc, self.gu = cfg, orc, gu
+        m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+        print("full-size schedule", cfg.name, m, d, k, b, cfg.storage, flush=True)
+        r = wl.rng(cfg, 29)
+        self.J = np.sort(r.choice(m, size=n_lab, replace=False))
+        self.I = np.sort(r.choice(b, size=n_inst, replace=False))
+        self.dJ, self.dI = torch.from_numpy(self.J).cuda(), torch.from_numpy(self.I).cuda()
+        self.L = usl.Layer(m, d, k, b, cfg.storage)
+        self.d_idx = gu.empty((m, k), torch.int32)
+        self.L.init_indices(self.d_idx, 1000 * cfg.index)
+        self.d_W = gu.dev(wl.gen_W(cfg))
+        self.d_m1, self.d_m2 = gu.dev(np.zeros((m, k), np.float32)), gu.dev(np.zeros((m, k), np.float32))
+        self.g, self.gW, self.gx, self.loss = gu.empty((b, m)), gu.empty((m, k)), gu.empty((b, d)), gu.empty((1,))
+        self.xs = [wl.gen_x(cfg, i) for i in range(cfg.n_x_batches)]
+        self.tg = [wl.gen_targets(cfg, i) for i in range(cfg.n_x_batches)]
+        self.d_xs = [gu.dev(x) for x in self.xs]
+        self.d_tg = [(gu.dev(o), gu.dev(l)) for o, l in self.tg]
+        self.scale = float(np.float32(1.0 / b))
+        self.seed = wl.redistribution_seed(cfg)
+        self.epoch = 0
+        self.t = 0
+
+    def step(self, check):
+        cfg, orc, gu, L = self.cfg, self.orc, self.gu, self.L
+        m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+        hp = wl.ADAM
+        J, I, dJ, dI = self.J, self.I, self.dJ, self.dI
+        self.t += 1
+        t = self.t
+        q = t % len(self.xs)
+        x, (off, lab) = self.xs[q], self.tg[q]
+        if check:   # the state the step starts from (idx and W in full: the input gradient needs them)
+            idx, W = gu.host(self.d_idx).copy(), gu.host(self.d_W).copy()
+            m1_J, m2_J = gu.host(self.d_m1.index_select(0, dJ)).copy(), gu.host(self.d_m2.index_select(0, dJ)).copy()
+        L.train_step(self.d_xs[q], self.d_idx, self.d_W, self.d_m1, self.d_m2, self.d_tg[q][0], self.d_tg[q][1], 0,
+                     self.scale, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], self.g, self.gW, self.gx, self.loss, b)
+        if check:
+            out_I = orc.forward(np.ascontiguousarray(x[I]), idx, W)
+            sub_off = np.zeros(len(I) + 1, np.int64)
+            sub_lab = []
+            for n, i in enumerate(I):
+                sub_lab.extend(lab[off[i]:off[i + 1]])
+                sub_off[n + 1] = len(sub_lab)
+            _, ref_g_I = orc.bce_loss_grad(out_I, sub_off, np.array(sub_lab, np.int32), self.scale)
+            g_I = gu.host(self.g.index_select(0, dI))
+            assert_close(g_I, ref_g_I, 1e-5, "g rows @%d" % t)
+            out_J = orc.forward(x, np.ascontiguousarray(idx[J]), np.ascontiguousarray(W[J]))
+            col = {int(j): n for n, j in enumerate(J)}
+            offJ, labJ = np.zeros(b + 1, np.int64), []
+            for i in range(b):
+                labJ.extend(col[int(l)] for l in lab[off[i]:off[i + 1]] if int(l) in col)
+                offJ[i + 1] = len(labJ)
+            _, ref_g_J = orc.bce_loss_grad(out_J, offJ, np.array(labJ if labJ else [0], np.int32), self.scale)
+            g_J = gu.host(self.g.index_select(1, dJ).contiguous())
+            assert_close(g_J, ref_g_J, 1e-5, "g cols @%d" % t)
+            gW_J = gu.host(self.gW.index_select(0, dJ))
+            assert_close(gW_J, orc.backward_weight(g_J, x, np.ascontiguousarray(idx[J])), 1e-5, "grad_W rows @%d" % t)
+            assert_close(gu.host(self.gx.index_select(0, dI)), orc.backward_input(g_I, idx, W, d), 1e-4,
+                         "grad_x rows @%d" % t)
+            W_J = np.ascontiguousarray(W[J])
+            pre = orc.adam_step(W_J, gW_J, m1_J, m2_J, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+            assert_close(gu.host(self.d_m1.index_select(0, dJ)), m1_J, 1e-4, "m1 @%d" % t)
+            assert_close(gu.host(self.d_m2.index_select(0, dJ)), m2_J, 1e-4, "m2 @%d" % t)
+            got = gu.host(self.d_W.index_select(0, dJ))
+            if cfg.storage == "f32":
+                assert_close(got, W_J, 1e-4, "W @%d" % t)
+            else:
+                assert_bf16_adam(got, pre)
+            assert np.isfinite(self.loss.item()) and self.loss.item() > 0
+            print("step", t, "ok", flush=True)
+        if wl.is_redistribution_step(cfg, t):
+            tensors = (self.d_idx, self.d_W, self.d_m1, self.d_m2)
+            h_idx, h_W, h_m1, h_m2 = (gu.host(a).copy() for a in tensors)
+            n = L.redistribute(*tensors, cfg.fraction, self.seed, self.epoch)
+            n_ref, _ = orc.redistribute(h_idx, h_W, h_m1, h_m2, d, cfg.fraction, self.seed, self.epoch)
+            assert n == n_ref
+            np.testing.assert_array_equal(gu.host(self.d_idx), h_idx)
+            np.testing.assert_array_equal(gu.host(self.d_W).view(np.uint8), h_W.view(np.uint8))
+            np.testing.assert_array_equal(gu.host(self.d_m1), h_m1)
+            np.testing.assert_array_equal(gu.host(self.d_m2), h_m2)
+            assert L.validate_indices(self.d_idx) == 0
+            self.epoch += 1
+            print("redistribution", self.epoch, "after step", t, "ok", flush=True)
+
+    def close(self):
+        self.L.close()
+        for name in ("g", "gW", "gx", "d_W", "d_m1", "d_m2", "d_idx", "d_xs", "d_tg"):
+            setattr(self, name, None)
+        torch.cuda.empty_cache()
+
+
+def run_full_schedule(cfg, orc, steps, check_steps, n_lab=2048, n_inst=2):
+    sch = FullSchedule(cfg, orc, n_lab, n_inst)
+    for t in range(1, steps + 1):
+        sch.step(t in check_steps)
+    sch.close()
+    return sch.epoch
+
+
+def test_large_schedule_two_redistributions(orc):
+    assert run_full_schedule(wl.CONFIGS["large"], orc, 20, {1, 10, 11, 20}) == 2
+
+
+def test_large_wide_schedule_two_redistributions(orc):
+    assert run_full_schedule(wl.CONFIGS["large_wide"], orc, 20, {1, 10, 11, 20}, n_lab=1024) == 2
+
+
+# Stress redistributes after every step and the oracle sorts 96 million magnitudes each time: one test per
+# step, sharing the schedule's state, so that no single test runs for minutes.
+_stress = {}
+
+
+@pytest.mark.parametrize("t", [1, 2, 3])
+def test_stress_schedule_step(orc, t):
+    if t == 1:
+        _stress["sch"] = FullSchedule(wl.CONFIGS["stress"], orc, n_lab=512)
+    sch = _stress.get("sch")
+    if sch is None or sch.t != t - 1:
+        pytest.skip("the earlier steps of this schedule did not run")
+    try:
+        sch.step(True)
+        assert sch.epoch == t
+    except BaseException:
+        _stress.pop("sch").close()
+        raise
+    if t == 3:
+        _stress.pop("sch").close()

@@ -393,9 +393,10 @@ def test_tiny_schedule(usl, gu, orc):
     assert run_schedule(usl, gu, orc, wl.CONFIGS["tiny"], 1) == 1
 
 
-def test_medium_schedule_prefix(usl, gu, orc):
-    """Config 1 (m=30938, d=1024, k=32, b=128): 20 of its 100 steps, two redistributions."""
-    assert run_schedule(usl, gu, orc, wl.CONFIGS["medium"], 20) == 2
+def test_medium_schedule(usl, gu, orc):
+    """Config 1 (m=30938, d=1024, k=32, b=128): all of its 100 steps, ten redistributions, every output of
+    every call compared in full."""
+    assert run_schedule(usl, gu, orc, wl.CONFIGS["medium"], 100) == 10
 
 
 def test_tiny_schedule_bf16(usl, gu, orc):
