@@ -27,13 +27,25 @@ def build(force=False):
     return _LIB
 
 
+def build_sanitized():
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (gcc), as a second library.
+    A process that loads it needs the sanitizer runtime preloaded; tests/test_oracle_sanitized.py does that
+    in a child process and points USL_ORACLE_LIB at the result."""
+    out = os.path.join(_HERE, "liboracle_san.so")
+    if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+             "-fno-omit-frame-pointer", "-shared", "-fPIC", "-o", out, _SRC, "-lm"])
+    return out
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(os.environ.get("USL_ORACLE_LIB") or build())
         _lib.orc_redistribute.restype = ctypes.c_int64
         _lib.orc_count_bad_rows.restype = ctypes.c_int64
         _lib.orc_draw_column.restype = ctypes.c_int32
