@@ -198,7 +198,8 @@ constexpr int GW_NT = 1024;
 template <typename TS>
 __global__ void __launch_bounds__(GW_NT)
 k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const uint32_t* __restrict__ ptr,
-           int d, int nwin, float* __restrict__ wl, int bpw) {
+           int d, int nwin, float* __restrict__ wl, int bpw, const uint32_t* __restrict__ gate) {
+    if (gate && *gate == 0) return;   // the sparse kernels do this call's work
     int w, local;
     if (nwin >= 8) {
         const int xcd = blockIdx.x & 7;
@@ -227,8 +228,10 @@ k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const ui
 
 // grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.x = tile, blockIdx.y = block of 32 features.
 __global__ void __launch_bounds__(256)
-k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, int64_t d) {
+k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, int64_t d,
+         const uint32_t* __restrict__ gate) {
     __shared__ float tile[32][33];
+    if (gate && *gate == 0) return;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int64_t i0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
 #pragma unroll
@@ -252,8 +255,9 @@ k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, i
 // blockIdx.y is the tile, so the 32 instances of a block are exactly one tile.
 __global__ void __launch_bounds__(256)
 k_transpose_g(const float* __restrict__ g, float* __restrict__ gT, int64_t b, int64_t m,
-              uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells) {
+              uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells, const uint32_t* __restrict__ gate) {
     __shared__ float tile[32][33];
+    if (gate && *gate == 0) return;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int64_t r0 = (int64_t)blockIdx.y * 32, c0 = (int64_t)blockIdx.x * 32;
 #pragma unroll
@@ -301,7 +305,9 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
                    const uint32_t* __restrict__ slot, int k, int kshift /* log2 k, or -1 */,
                    float* __restrict__ gxT, int d, int tile0,
                    int accumulate, const uint8_t* __restrict__ nzf /* this tile row is nzf + tile*m */,
-                   int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below) {
+                   int64_t m, const uint32_t* __restrict__ nz_cells, uint32_t sparse_below,
+                   const uint32_t* __restrict__ gate) {
+    if (gate && *gate == 0) return;
     const int rank = SPLIT == 1 ? blockIdx.y * 32 + (threadIdx.x >> 3) : blockIdx.y * 4 + (threadIdx.x >> 6);
     if (rank >= d) return;   // SPLIT = 8: the whole wavefront leaves
     const int c = (int)order[rank];
@@ -495,7 +501,8 @@ usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
 
 // The gathers, once gT, the piece flags and the sampled count of nonzero pieces are in place.
 // sampled_labels = how many labels the count covers (per tile).
-usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels) {
+usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels,
+                             const uint32_t* gate) {
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
     const int ntile = (b + 31) / 32;
@@ -507,10 +514,10 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
         const unsigned blocks = (unsigned)(nwin >= 8 ? (nwin + 7) / 8 * 8 : nwin) * bpw;
         if (c->storage == USL_F32)
             hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate);
         else
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate);
     }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
@@ -527,18 +534,18 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
                     hipLaunchKernelGGL(k_bwd_input_window<8>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
                                        c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
                                        c->k, kshift, c->gxT, c->d, t0,
-                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
                 else
                     hipLaunchKernelGGL(k_bwd_input_window<1>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
                                        c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
                                        c->k, kshift, c->gxT, c->d, t0,
-                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below);
+                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
             }
         }
     }
     {
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
-        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d);
+        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d, gate);
     }
     return usl_check_launch(c, "backward_input");
 }
@@ -546,10 +553,17 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
 usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
                                      float* grad_x, int32_t b) {
     USL_TRY(usl_bwd_input_prepare(c, idx, b));
+    // a gradient that is almost all zeros goes through per-instance lists of its nonzeros instead; which of the
+    // two paths does the work is decided on the device (gate), both are enqueued
+    const uint32_t* gate = nullptr;
+    if (usl_sparse_supported(c)) {
+        USL_TRY(usl_sparse_compact(c, g, b, &gate));
+        USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
+    }
     {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
         dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));
         hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
-                           c->nz_flags, usl_nz_cells(c));
+                           c->nz_flags, usl_nz_cells(c), gate);
     }
-    return usl_bwd_input_run(c, W, grad_x, b, (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32);
+    return usl_bwd_input_run(c, W, grad_x, b, (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32, gate);
 }

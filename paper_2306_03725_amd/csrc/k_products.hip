@@ -290,9 +290,11 @@ template <int K, int LPT, int NT, typename TS, int MODE, bool ATOMIC, bool SKIP>
 __global__ void __launch_bounds__(NT)
 k_backward_weight(const float* __restrict__ g, const TS* __restrict__ x,
                   const int32_t* __restrict__ idx, float* __restrict__ grad_W, int64_t m, int d,
-                  int b, TileGeom tg, const uint8_t* __restrict__ perm, int64_t part_stride) {
+                  int b, TileGeom tg, const uint8_t* __restrict__ perm, int64_t part_stride,
+                  const uint32_t* __restrict__ gate) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     TS* lds = reinterpret_cast<TS*>(lds_raw);
+    if (gate && *gate == 0) return;   // the gradient is almost all zeros: the kernels over its nonzeros do the work
     if ((MODE == 0 || MODE == 1) && sizeof(TS) == 4 && !lds_starts_at_zero(lds_raw)) return;   // see gather_row0
     // sliced float32 rows are exactly two halves of 32768 columns (the fast path stops at d = 65536)
     constexpr bool HALVES = MODE == 1 && sizeof(TS) == 4 && USL_ROW_LDS_BYTES == 131072;
@@ -733,6 +735,14 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     const size_t N = (size_t)c->m * c->k;
     int64_t part_stride = 0;
     float* dst = grad_W;
+    // one group of instances per label block (the large layers): a gradient that may be almost all zeros is first
+    // tried through the lists of its nonzeros; the device decides which path does the work
+    const uint32_t* gate = nullptr;
+    if (!dense && G == 1 && usl_sparse_supported(c)) {
+        if (c->nz_lists_of == g) gate = c->nz_state;
+        else USL_TRY(usl_sparse_compact(c, g, b, &gate));
+        USL_TRY(usl_sparse_backward_weight(c, x, idx, grad_W, b));
+    }
     if (G > 1 && (size_t)G * N * 4 <= ((size_t)1 << 29) && N % 4 == 0 && (uintptr_t)grad_W % 16 == 0) {
         USL_TRY(usl_reserve(c, (void**)&c->gw_part, &c->gw_part_cap, (size_t)G * N * 4));
         part_stride = (int64_t)N;
@@ -754,11 +764,11 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
         if (dense && DENSE_OK) {                                                                        \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>, lds));         \
             hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, !DENSE_OK>), grid, dim3(NT), lds, \
-                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride); \
+                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride, gate); \
         } else {                                                                                        \
             USL_TRY(allow_lds(c, k_backward_weight<K, LPT, NT, TS, MODE, AT, true>, lds));              \
             hipLaunchKernelGGL((k_backward_weight<K, LPT, NT, TS, MODE, AT, true>), grid, dim3(NT), lds, \
-                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride); \
+                               c->stream, g, (const TS*)x, idx, dst, c->m, c->d, b, tg, perm, part_stride, gate); \
         }                                                                                               \
     } while (0)
     const int mode = tg.nparts > 1 ? 1 : ((LPT == 1 && tg.rows_per_tile > 1) ? 2 : (tg.buf_stride && LPT > 1 ? 3 : 0));

@@ -31,7 +31,8 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
     if (c->device >= 0) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
-                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part};
+                        c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part,
+                        c->nz_state, c->nz_lab, c->nz_val};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
@@ -336,8 +337,18 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
         uint64_t sampled = 0;
         USL_TRY(usl_bwd_input_prepare(c, idx, b));
         USL_TRY(usl_launch_loss_tiles(c, loss_kind, g, tgt_off, tgt_lab, scale, loss, b, &sampled));
-        USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0));   // BCE gradients are dense
-        USL_TRY(usl_bwd_input_run(c, W, grad_x, b, sampled));
+        // squared hinge: the gradient of a trained layer is almost all zeros (Section 3.3); its nonzeros are listed
+        // once and both backward products try the lists first (the device decides, see k_sparse_grad.hip)
+        const uint32_t* gate = nullptr;
+        if (loss_kind == 1 && usl_sparse_supported(c)) {
+            USL_TRY(usl_sparse_compact(c, g, b, &gate));
+            c->nz_lists_of = g;
+        }
+        usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);   // BCE gradients are dense
+        c->nz_lists_of = nullptr;
+        USL_TRY(s);
+        if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
+        USL_TRY(usl_bwd_input_run(c, W, grad_x, b, sampled, gate));
     } else {
         USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
         USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0));   // BCE gradients are dense

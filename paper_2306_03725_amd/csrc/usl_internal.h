@@ -47,6 +47,11 @@ struct usl_ctx {
     uint64_t* topk_cand;      size_t topk_cand_cap;  // [b][segments][kk] packed (score, label) keys
     float* gw_part;           size_t gw_part_cap;   // [groups][m*k] partial weight gradients of a split batch
     float* gxT;               size_t gxT_cap;  // [tiles][d][32] input gradient in the same layout
+    // per-instance lists of the nonzero entries of g (k_sparse_grad.hip)
+    uint32_t* nz_state;       size_t nz_state_cap;   // [0] = 1: gradient is dense, lists abandoned; [16+i] = entries of instance i
+    int32_t* nz_lab;          size_t nz_lab_cap;     // [max_b][m/32] label of an entry
+    float* nz_val;            size_t nz_val_cap;     // [max_b][m/32] its gradient
+    const float* nz_lists_of; // g whose lists are current (only set inside usl_train_step), else NULL
 };
 
 #define USL_FAIL(ctx, code, ...)                                   \
@@ -84,9 +89,17 @@ usl_status usl_launch_backward_weight(usl_ctx* ctx, const float* g, const void* 
                                       const int32_t* idx, float* grad_W, int32_t b, bool dense = false);
 usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx,
                                      const void* W, float* grad_x, int32_t b);
+// The products over the nonzero entries of g only (k_sparse_grad.hip).  usl_sparse_compact builds the lists (or
+// finds g dense); *gate is a device word, 0 = the lists stand and the sparse kernels do the work, 1 = the dense
+// kernels have to.  Dense kernels that are handed the gate leave at once when it reads 0.
+bool usl_sparse_supported(const usl_ctx* ctx);
+usl_status usl_sparse_compact(usl_ctx* ctx, const float* g, int32_t b, const uint32_t** gate);
+usl_status usl_sparse_backward_weight(usl_ctx* ctx, const void* x, const int32_t* idx, float* grad_W, int32_t b);
+usl_status usl_sparse_backward_input(usl_ctx* ctx, const int32_t* idx, const void* W, float* grad_x, int32_t b);
 // backward_input in two halves, for callers that produce gT / nz_flags / the nonzero count themselves
 usl_status usl_bwd_input_prepare(usl_ctx* ctx, const int32_t* idx, int32_t b);
-usl_status usl_bwd_input_run(usl_ctx* ctx, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels);
+usl_status usl_bwd_input_run(usl_ctx* ctx, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels,
+                             const uint32_t* gate = nullptr);
 static inline uint32_t* usl_nz_cells(usl_ctx* c) { return reinterpret_cast<uint32_t*>(c->counter64) + 4; }
 // Loss and gradient in place on zg[b][m], which also leaves the gradient in c->gT (tile-major) with
 // its piece flags and sampled nonzero count (usl_bwd_input_prepare must have run); *sampled_labels

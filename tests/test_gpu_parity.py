@@ -162,7 +162,10 @@ def test_squared_hinge(usl, gu, orc, name):
 
 
 SPARSE_G = [("tiny", "f32", 0.9), ("ragged_small", "f32", 0.99), ("k64", "f32", 0.97), ("big_blocks", "f32", 0.999),
-            ("big_one_group", "f32", 0.9), ("sliced_small", "bf16", 0.95), ("k5", "f32", 0.9), ("big_blocks", "bf16", 1.0)]
+            ("big_one_group", "f32", 0.9), ("sliced_small", "bf16", 0.95), ("k5", "f32", 0.9), ("big_blocks", "bf16", 1.0),
+            # few enough nonzeros for the per-instance lists (99 % and more zeros on a layer of >= 65536 labels)
+            ("big_one_group", "f32", 0.99), ("big_one_group", "f32", 0.999), ("big_one_group", "bf16", 0.995),
+            ("big_blocks", "f32", 0.995), ("sliced_big", "f32", 0.99), ("big_one_group", "f32", 1.0)]
 
 
 @pytest.mark.parametrize("name,storage,zero_frac", SPARSE_G)
@@ -178,6 +181,8 @@ def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_fr
     g[:, : m // 3] = 0.0                             # a range of labels that contributes nothing
     if b > 2:
         g[b - 1, m - 1] = 0.25                       # ... and a lone survivor at the very end
+    if zero_frac == 1.0 and name == "big_one_group":
+        g[:] = 0.0                                   # nothing at all
     L = usl.Layer(m, d, k, b, storage)
     d_idx, d_W, d_x, d_g = gu.dev(idx), gu.dev(W), gu.dev(x), gu.dev(g)
     gW = gu.empty((m, k)).fill_(float("nan"))
@@ -186,10 +191,28 @@ def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_fr
     L.backward_input(d_g, d_idx, d_W, gx, b)
     assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W")
     assert_close(gu.host(gx), orc.backward_input(g, idx, W, d), 1e-4, "grad_x")
+    # one instance dense among sparse ones: its list overflows and the dense kernels take over
+    if m >= 65536 and zero_frac >= 0.99:
+        g3 = g.copy()
+        g3[0] = wl.gen_g(cfg, 2)[0]
+        d_g3 = gu.dev(g3)
+        gW.fill_(float("nan")); gx.fill_(float("nan"))
+        L.backward_weight(d_g3, d_x, d_idx, gW, b)
+        L.backward_input(d_g3, d_idx, d_W, gx, b)
+        assert_close(gu.host(gW), orc.backward_weight(g3, x, idx), 1e-5, "grad_W, one dense instance")
+        assert_close(gu.host(gx), orc.backward_input(g3, idx, W, d), 1e-4, "grad_x, one dense instance")
+        # ... and sparse again
+        gW.fill_(float("nan")); gx.fill_(float("nan"))
+        L.backward_weight(d_g, d_x, d_idx, gW, b)
+        L.backward_input(d_g, d_idx, d_W, gx, b)
+        assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W sparse again")
+        assert_close(gu.host(gx), orc.backward_input(g, idx, W, d), 1e-4, "grad_x sparse again")
     # dense again on the same context: the sparse path must not stick
     g2 = wl.gen_g(cfg, 1)
     L.backward_input(gu.dev(g2), d_idx, d_W, gx, b)
     assert_close(gu.host(gx), orc.backward_input(g2, idx, W, d), 1e-4, "grad_x dense after sparse")
+    L.backward_weight(gu.dev(g2), d_x, d_idx, gW, b)
+    assert_close(gu.host(gW), orc.backward_weight(g2, x, idx), 1e-5, "grad_W dense after sparse")
 
 
 @pytest.mark.parametrize("storage", ["f32", "bf16"])

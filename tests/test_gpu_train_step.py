@@ -19,6 +19,9 @@ CASES = [
     (270001, 2048, 32, 9, "f32", 0, True, False),
     (270000, 2048, 32, 33, "f32", 1, False, False),    # no input gradient
     (2000, 40000, 16, 3, "bf16", 1, True, False),
+    (400001, 4096, 32, 5, "f32", 1, True, True),       # large layer, squared hinge, easy negatives: the lists of nonzeros
+    (400000, 4096, 64, 3, "bf16", 1, True, True),
+    (400000, 70000, 16, 2, "f32", 1, True, True),      # ... with an input row wider than one LDS slice
 ]
 
 
