@@ -48,13 +48,16 @@ typedef enum {
     USL_ESHAPE = 2,       /* sizes the library cannot take (k > d, b > max_b, m*k too large...) */
     USL_ENOMEM = 3,       /* host or device allocation failed */
     USL_EHIP = 4,         /* a HIP call failed (message in usl_last_error), or no GPU */
-    USL_EUNSUPPORTED = 5  /* a valid request this build has no kernel for */
+    USL_EUNSUPPORTED = 5, /* a valid request this build has no kernel for */
+    USL_ESTALE = 6        /* usl_check: idx was rewritten without usl_invalidate (see there) */
 } usl_status;
 
 typedef enum { USL_F32 = 0, USL_BF16 = 1 } usl_dtype; /* storage of x and W; sums are float32 */
 
 /* Create a context for a layer of m labels, input width d, fan-in k, batches of at most
- * max_b instances.  Limits: 1 <= k <= d <= 2^24, 1 <= m, m*k < 2^32, max_b >= 1.
+ * max_b instances.  Limits: 1 <= k <= d <= 2^24, 1 <= m, m*k < 2^32, 1 <= max_b <= 65535.
+ * Scratch that depends on the batch is sized for max_b when it is first needed, so that a later, larger
+ * batch never makes a call reallocate (which would wait for the stream).
  * hip_stream is a hipStream_t (NULL = the null stream).  No device memory is touched until
  * the first call that launches; a context can be created on a host without a GPU. */
 usl_status usl_create(usl_ctx** ctx, int64_t m, int32_t d, int32_t k, int32_t max_b,
@@ -67,6 +70,14 @@ usl_status usl_set_stream(usl_ctx* ctx, void* hip_stream);
  * the contents of idx by any other means must call this before the next product call: a stale
  * column-major copy gives wrong input gradients (a stale visiting order only costs speed). */
 usl_status usl_invalidate(usl_ctx* ctx);
+/* The address alone cannot tell an idx array from another one that an allocator later placed at the same
+ * address, or from a checkpoint copied into it.  As a safety net every usl_backward_input on an address it
+ * already has lists for re-reads a sample of idx (64 KiB) on the device and compares its fingerprint with the
+ * one taken when the lists were built; on a mismatch that call fills grad_x with NaN instead of numbers from
+ * stale lists, and the condition stays recorded.  usl_check waits for the stream and returns USL_ESTALE if
+ * that happened since the last check (and invalidates the private views), USL_OK otherwise.  A change of a
+ * single entry can escape the sample: usl_invalidate remains the contract, this is the net under it. */
+usl_status usl_check(usl_ctx* ctx);
 const char* usl_last_error(const usl_ctx* ctx); /* never NULL; owned by the context */
 const char* usl_version(void);
 

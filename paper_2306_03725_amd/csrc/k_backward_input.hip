@@ -34,6 +34,51 @@ __global__ void k_zero_u32(uint32_t* p, size_t n) {
     for (; i < n; i += s) p[i] = 0;
 }
 
+// Fingerprint of idx: a sum of mixed 16-byte groups at up to 4096 evenly spaced places (64 KiB read by one
+// workgroup, every load in flight at once: a few microseconds).  store = 1 records it when the column lists
+// are built; store = 0 compares on a later call and raises print[2] (as a 32-bit word) when the contents are
+// no longer those the lists were built from: a new tensor at a recycled address, a checkpoint copied in, ...
+// A single edited entry can slip through the sample; wholesale replacement cannot.
+__device__ __forceinline__ void idx_fingerprint_block(const uint32_t* __restrict__ idx, size_t n_words,
+                                                      uint64_t* __restrict__ print, int store) {   // 1024 lanes
+    __shared__ uint64_t red[16];
+    const size_t groups = n_words / 4;
+    const size_t samples = groups < 4096 ? groups : 4096;
+    const size_t stride = samples ? groups / samples : 1;   // >= 1
+    uint4 v[4];
+    size_t at[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const size_t s = (size_t)q * 1024 + threadIdx.x;
+        at[q] = s < samples ? s * stride : 0;
+        v[q] = s < samples ? reinterpret_cast<const uint4*>(idx)[at[q]] : make_uint4(0, 0, 0, 0);
+    }
+    uint64_t h = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if ((size_t)q * 1024 + threadIdx.x >= samples) continue;
+        uint64_t a = ((uint64_t)v[q].x << 32 | v[q].y) ^ (at[q] * 0x9E3779B97F4A7C15ull);
+        uint64_t b2 = ((uint64_t)v[q].z << 32 | v[q].w) + (at[q] << 7);
+        a ^= a >> 31; a *= 0xD6E8FEB86659FD93ull; a ^= a >> 29;
+        b2 ^= b2 >> 33; b2 *= 0xC2B2AE3D27D4EB4Full; b2 ^= b2 >> 30;
+        h += a + (b2 << 1 | b2 >> 63);
+    }
+    for (size_t w = groups * 4 + threadIdx.x; w < n_words; w += 1024) h += (uint64_t)idx[w] * 0xFF51AFD7ED558CCDull;   // ragged tail
+    for (int o = 32; o > 0; o >>= 1) h += __shfl_down(h, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = h;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t t = 0;
+        for (int q = 0; q < 16; ++q) t += red[q];
+        if (store) { print[0] = t; }
+        else if (print[0] != t) reinterpret_cast<uint32_t*>(print)[4] = 1u;
+    }
+}
+__global__ void __launch_bounds__(1024)
+k_idx_fingerprint(const uint32_t* __restrict__ idx, size_t n_words, uint64_t* __restrict__ print, int store) {
+    idx_fingerprint_block(idx, n_words, print, store);
+}
+
 // Lists are grouped by (label window, feature).  A workgroup takes one of `splits` equal shares of
 // a window's slots (contiguous in idx) and a chunk of up to 32768 features, and counts its share in
 // an LDS histogram; global memory sees one coalesced atomic per (workgroup, feature), not one per slot.
@@ -198,8 +243,11 @@ constexpr int GW_NT = 1024;
 template <typename TS>
 __global__ void __launch_bounds__(GW_NT)
 k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const uint32_t* __restrict__ ptr,
-           int d, int nwin, float* __restrict__ wl, int bpw, const uint32_t* __restrict__ gate) {
+           int d, int nwin, float* __restrict__ wl, int bpw, const uint32_t* __restrict__ gate,
+           const uint32_t* __restrict__ idx_check /* or NULL */, size_t n_words, uint64_t* __restrict__ print) {
     if (gate && *gate == 0) return;   // the sparse kernels do this call's work
+    // the first workgroup also checks that idx still holds what the lists were built from (see idx_fingerprint_block)
+    if (idx_check && blockIdx.x == 0) idx_fingerprint_block(idx_check, n_words, print, 0);
     int w, local;
     if (nwin >= 8) {
         const int xcd = blockIdx.x & 7;
@@ -229,9 +277,10 @@ k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const ui
 // grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.x = tile, blockIdx.y = block of 32 features.
 __global__ void __launch_bounds__(256)
 k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, int64_t d,
-         const uint32_t* __restrict__ gate) {
+         const uint32_t* __restrict__ gate, const uint32_t* __restrict__ stale) {
     __shared__ float tile[32][33];
     if (gate && *gate == 0) return;
+    const bool poison = *stale != 0;   // the lists were built from other contents of idx: no number is better than a wrong one
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int64_t i0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
 #pragma unroll
@@ -243,7 +292,7 @@ k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, i
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int64_t i = i0 + ty + 8 * q, c = c0 + tx;
-        if (i < b && c < d) grad_x[i * d + c] = tile[tx][ty + 8 * q];
+        if (i < b && c < d) grad_x[i * d + c] = poison ? __uint_as_float(0x7FC00000u) : tile[tx][ty + 8 * q];
     }
 }
 
@@ -477,6 +526,13 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
     hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
     hipLaunchKernelGGL(k_csc_fill, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
                        splits, c->csc_ptr, rank_of, c->csc_cursor, c->csc_slot);
+    if (!c->idx_print) {
+        size_t cap = 0;
+        USL_TRY(usl_reserve(c, (void**)&c->idx_print, &cap, 64));
+        hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<uint32_t*>(c->idx_print), (size_t)16);
+    }
+    hipLaunchKernelGGL(k_idx_fingerprint, dim3(1), dim3(1024), 0, c->stream, reinterpret_cast<const uint32_t*>(idx), N,
+                       c->idx_print, 1);
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
     return USL_OK;
@@ -486,8 +542,14 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
 
 // Lists for this idx, and the scratch a call with batch b needs; clears the nonzero-piece counter.
 usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
-    if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) USL_TRY(build_csc(c, idx));
-    const int ntile = (b + 31) / 32;
+    if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) {
+        USL_TRY(build_csc(c, idx));
+        c->idx_to_check = nullptr;
+    } else {   // same address as when the lists were built: the weight gather checks that the contents are the same
+        c->idx_to_check = idx;
+    }
+    (void)b;
+    const int ntile = (c->max_b + 31) / 32;   // sized once for the largest batch: a later call never has to grow them
     USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)ntile * c->m * 32 * 4));
     USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)ntile * c->d * 32 * 4));
     USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
@@ -514,10 +576,12 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
         const unsigned blocks = (unsigned)(nwin >= 8 ? (nwin + 7) / 8 * 8 : nwin) * bpw;
         if (c->storage == USL_F32)
             hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
+                               reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
         else
             hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate);
+                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
+                               reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
     }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
@@ -545,7 +609,8 @@ usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b
     }
     {
         dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
-        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d, gate);
+        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d, gate,
+                           reinterpret_cast<const uint32_t*>(c->idx_print) + 4);
     }
     return usl_check_launch(c, "backward_input");
 }
@@ -558,7 +623,7 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
     const uint32_t* gate = nullptr;
     if (usl_sparse_supported(c)) {
         USL_TRY(usl_sparse_compact(c, g, b, &gate));
-        USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
+        if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
     }
     {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
         dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));

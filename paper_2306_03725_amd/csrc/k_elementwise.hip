@@ -271,13 +271,19 @@ k_adam(TS* __restrict__ W, const float* __restrict__ gW, float* __restrict__ m1,
 
 }  // namespace
 
+// Per-block loss sums of either loss kernel, sized once for max_b instances: a later, larger batch never
+// has to grow the buffer (growing frees and allocates, which waits for the stream).
+static usl_status usl_reserve_loss_partials(usl_ctx* c) {
+    const size_t rows = (size_t)((c->m + BCE_CHUNK - 1) / BCE_CHUNK) * (size_t)c->max_b;
+    const size_t tiles = (size_t)((c->m + LT_TL - 1) / LT_TL) * (size_t)((c->max_b + 31) / 32);
+    return usl_reserve(c, (void**)&c->bce_partials, &c->bce_partials_cap, (rows > tiles ? rows : tiles) * sizeof(double));
+}
+
 usl_status usl_launch_loss(usl_ctx* c, int loss_kind, const float* out, const int64_t* tgt_off,
                            const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b) {
     const int64_t nchunk = (c->m + BCE_CHUNK - 1) / BCE_CHUNK;
     const size_t nblk = (size_t)nchunk * b;
-    size_t cap = c->bce_partials_cap;
-    USL_TRY(usl_reserve(c, (void**)&c->bce_partials, &cap, nblk * sizeof(double)));
-    c->bce_partials_cap = cap;
+    USL_TRY(usl_reserve_loss_partials(c));
     const bool vec = (c->m % 4 == 0) && ((uintptr_t)out % 16 == 0) && ((uintptr_t)g % 16 == 0);
     dim3 grid((unsigned)nchunk, (unsigned)b);
 #define USL_LOSS(VEC, KIND)                                                                          \
@@ -338,9 +344,7 @@ usl_status usl_launch_loss_tiles(usl_ctx* c, int loss_kind, float* zg, const int
     const int64_t nlb = (c->m + LT_TL - 1) / LT_TL;
     const int ntile = (b + 31) / 32;
     const size_t nblk = (size_t)nlb * ntile;
-    size_t cap = c->bce_partials_cap;
-    USL_TRY(usl_reserve(c, (void**)&c->bce_partials, &cap, nblk * sizeof(double)));
-    c->bce_partials_cap = cap;
+    USL_TRY(usl_reserve_loss_partials(c));
     const bool vec = (c->m % 4 == 0) && ((uintptr_t)zg % 16 == 0);
     dim3 grid((unsigned)nlb, (unsigned)ntile);
 #define USL_LOSS(VEC, KIND)                                                                              \

@@ -162,7 +162,8 @@ int usl_topk_max(void) { return TK_MAX; }
 usl_status usl_launch_topk(usl_ctx* c, const float* out, int32_t b, int32_t kk, int32_t* top_lab,
                            float* top_val) {
     const int nseg = (int)((c->m + TK_SEG - 1) / TK_SEG);
-    USL_TRY(usl_reserve(c, (void**)&c->topk_cand, &c->topk_cand_cap, (size_t)b * nseg * kk * 8));
+    // sized once for the largest batch and the largest kk, so that no later call has to grow it (growing waits for the stream)
+    USL_TRY(usl_reserve(c, (void**)&c->topk_cand, &c->topk_cand_cap, (size_t)c->max_b * nseg * TK_MAX * 8));
     if (c->m % 4 == 0 && (uintptr_t)out % 16 == 0)
         hipLaunchKernelGGL(k_topk_segments<true>, dim3((unsigned)nseg, (unsigned)b), dim3(TK_NT), 0, c->stream, out,
                            c->m, (int)kk, nseg, c->topk_cand);

@@ -739,12 +739,16 @@ usl_status run_backward_weight(usl_ctx* c, const float* g, const void* x, const 
     // tried through the lists of its nonzeros; the device decides which path does the work
     const uint32_t* gate = nullptr;
     if (!dense && G == 1 && usl_sparse_supported(c)) {
-        if (c->nz_lists_of == g) gate = c->nz_state;
+        if (c->nz_lists_of == g) gate = c->nz_lists_tried ? c->nz_state : nullptr;
         else USL_TRY(usl_sparse_compact(c, g, b, &gate));
-        USL_TRY(usl_sparse_backward_weight(c, x, idx, grad_W, b));
+        if (gate) USL_TRY(usl_sparse_backward_weight(c, x, idx, grad_W, b));
     }
     if (G > 1 && (size_t)G * N * 4 <= ((size_t)1 << 29) && N % 4 == 0 && (uintptr_t)grad_W % 16 == 0) {
-        USL_TRY(usl_reserve(c, (void**)&c->gw_part, &c->gw_part_cap, (size_t)G * N * 4));
+        size_t lds_max;
+        int Gmax = G;   // groups a batch of max_b instances would be split into: sized once, never grown by a later call
+        (void)plan(c, (int)sizeof(TS), c->max_b, nblk, x, &lds_max, &Gmax, LPT == 1);
+        if ((size_t)Gmax * N * 4 > ((size_t)1 << 29) || Gmax < G) Gmax = G;
+        USL_TRY(usl_reserve(c, (void**)&c->gw_part, &c->gw_part_cap, (size_t)Gmax * N * 4));
         part_stride = (int64_t)N;
         dst = c->gw_part;
     } else if (G > 1) {

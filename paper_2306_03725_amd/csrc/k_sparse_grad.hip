@@ -13,6 +13,8 @@
 //   3. the dense kernels are launched all the same and leave at their first instruction when the lists
 //      stand (and the other way round): `gate` below.
 // Results equal the dense sums up to the order of the additions (a skipped term is 0 * finite).
+#include <stdlib.h>
+
 #include "usl_internal.h"
 
 namespace {
@@ -23,7 +25,9 @@ constexpr int CG_NT = 256, CG_PER = 32, CG_CHUNK = CG_NT * CG_PER;   // labels p
 // common case after binary cross-entropy, is recognised here and the full pass leaves at its first instruction.
 // state[0] = 1 once the gradient counts as dense; state[16 + i] = entries listed for instance i.
 __global__ void __launch_bounds__(256)
-k_probe_density(const float* __restrict__ g, int64_t m, uint32_t* __restrict__ state) {
+k_probe_density(const float* __restrict__ g, int64_t m, uint32_t* __restrict__ state,
+                uint32_t* __restrict__ hint /* pinned host memory: [0] serial of the last finished look, [1] its verdict */,
+                uint32_t serial) {
     __shared__ uint32_t seen, hit;
     if (threadIdx.x == 0) { seen = 0; hit = 0; }
     __syncthreads();
@@ -38,7 +42,17 @@ k_probe_density(const float* __restrict__ g, int64_t m, uint32_t* __restrict__ s
     atomicAdd(&hit, nz);
     __syncthreads();
     // the lists hold m/32 entries per instance: a sample twice as dense as that cannot fit
-    if (threadIdx.x == 0 && seen >= 128 && (uint64_t)hit * 16 > seen) atomicOr(&state[0], 1u);
+    if (threadIdx.x == 0) {
+        if (seen >= 128 && (uint64_t)hit * 16 > seen) atomicOr(&state[0], 1u);
+        // what the host reads before its next call: would lists have been worth trying?  (sample at most 1/64 nonzero)
+        if ((uint64_t)hit * 64 > seen) atomicOr(&state[2], 1u);
+        __threadfence();
+        if (atomicAdd(&state[1], 1u) == gridDim.x - 1) {   // the last instance's block
+            hint[1] = atomicOr(&state[2], 0u) != 0 ? 1u : 0u;
+            __threadfence_system();
+            hint[0] = serial;
+        }
+    }
 }
 
 __global__ void __launch_bounds__(CG_NT)
@@ -183,15 +197,43 @@ bool usl_sparse_supported(const usl_ctx* c) {
     return c->m >= 65536 && (size_t)c->max_b * list_capacity(c) * 8 <= ((size_t)4 << 30);
 }
 
-// Builds the lists of g[b][m] (or finds the gradient dense).  *gate receives the device word that is 0 when the
-// lists stand and 1 when the dense kernels have to run.
+// Looks at g[b][m] and, if the context has reason to expect a gradient that is almost all zeros, builds the
+// lists of its nonzeros.  Every call enqueues the sample look (a few microseconds), whose verdict reaches the host
+// through two pinned words that the NEXT calls read without waiting: after two such looks in a row that found
+// the sample sparse the lists are tried, and the first look that finds it dense ends that.  A gradient that turns
+// sparse is therefore handled by the dense kernels for two more calls, one that turns dense by the gated dense
+// kernels once -- never wrongly, and a steadily dense gradient (binary cross-entropy) pays for the sample only.
+// *gate: NULL = only the dense kernels run this time; else the device word that is 0 when the lists stand and 1
+// when the dense kernels (which are then enqueued behind the gate) have to do the work.
+// USL_TUNE_SPARSE=always / never overrides the expectation (tests, profiling).
 usl_status usl_sparse_compact(usl_ctx* c, const float* g, int32_t b, const uint32_t** gate) {
     const uint32_t cap = list_capacity(c);
+    *gate = nullptr;
+    if (!c->hint_host) {
+        USL_HIP(c, hipHostMalloc((void**)&c->hint_host, 64, hipHostMallocMapped));
+        c->hint_host[0] = 0; c->hint_host[1] = 1;
+        USL_HIP(c, hipHostGetDevicePointer((void**)&c->hint_dev, c->hint_host, 0));
+    }
     USL_TRY(usl_reserve(c, (void**)&c->nz_state, &c->nz_state_cap, ((size_t)c->max_b + 16) * 4));
+    {   // what earlier looks found (whichever of them have finished by now)
+        const volatile uint32_t* h = c->hint_host;
+        const uint32_t serial = h[0], dense = h[1];
+        if (serial != c->hint_seen) {
+            c->hint_seen = serial;
+            c->sparse_streak = dense ? 0 : c->sparse_streak + 1;
+        }
+    }
+    bool try_lists = c->sparse_streak >= 2;
+    if (const char* e = getenv("USL_TUNE_SPARSE")) {
+        if (!strcmp(e, "always")) try_lists = true;
+        else if (!strcmp(e, "never")) try_lists = false;
+    }
+    hipLaunchKernelGGL(k_zero_state, dim3(1), dim3(256), 0, c->stream, c->nz_state, (size_t)b + 16);
+    hipLaunchKernelGGL(k_probe_density, dim3((unsigned)b), dim3(256), 0, c->stream, g, c->m, c->nz_state, c->hint_dev,
+                       ++c->probe_serial);
+    if (!try_lists) return usl_check_launch(c, "gradient sample");
     USL_TRY(usl_reserve(c, (void**)&c->nz_lab, &c->nz_lab_cap, (size_t)c->max_b * cap * 4));
     USL_TRY(usl_reserve(c, (void**)&c->nz_val, &c->nz_val_cap, (size_t)c->max_b * cap * 4));
-    hipLaunchKernelGGL(k_zero_state, dim3(1), dim3(256), 0, c->stream, c->nz_state, (size_t)b + 16);
-    hipLaunchKernelGGL(k_probe_density, dim3((unsigned)b), dim3(256), 0, c->stream, g, c->m, c->nz_state);
     dim3 grid((unsigned)((c->m + CG_CHUNK - 1) / CG_CHUNK), (unsigned)b);
     hipLaunchKernelGGL(k_compact_g, grid, dim3(CG_NT), 0, c->stream, g, c->m, cap, c->nz_state, c->nz_lab, c->nz_val);
     *gate = c->nz_state;

@@ -13,6 +13,7 @@ extern "C" usl_status usl_create(usl_ctx** out, int64_t m, int32_t d, int32_t k,
     if (storage != USL_F32 && storage != USL_BF16) return USL_EINVAL;
     if (m < 1 || d < 1 || k < 1 || max_b < 1) return USL_EINVAL;
     if (k > d || d > (1 << 24) || m > 0x7FFFFFFFll) return USL_ESHAPE;
+    if (max_b > 65535) return USL_ESHAPE;   // the instance is a grid dimension of several kernels
     if (m * (int64_t)k >= (int64_t)1 << 32) return USL_ESHAPE;
     usl_ctx* c = (usl_ctx*)calloc(1, sizeof(usl_ctx));
     if (!c) return USL_ENOMEM;
@@ -32,10 +33,11 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
                         c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part,
-                        c->nz_state, c->nz_lab, c->nz_val};
+                        c->nz_state, c->nz_lab, c->nz_val, c->idx_print};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
+        if (c->hint_host) (void)hipHostFree(c->hint_host);
     }
     free(c);
     return USL_OK;
@@ -189,7 +191,9 @@ extern "C" usl_status usl_predict(usl_ctx* c, const void* x, const int32_t* idx,
     }
     const int64_t cap_rows = (int64_t)(cap_bytes / ((size_t)c->m * 4));
     const int chunk = (int)(b <= 64 || cap_rows >= b ? b : (cap_rows < 64 ? 64 : cap_rows));
-    USL_TRY(usl_reserve(c, (void**)&c->predict_out, &c->predict_out_cap, (size_t)chunk * c->m * 4));
+    const int mb = c->max_b;   // the scratch takes the chunk of the largest batch, so that no later call has to grow it
+    const int chunk_max = (int)(mb <= 64 || cap_rows >= mb ? mb : (cap_rows < 64 ? 64 : cap_rows));
+    USL_TRY(usl_reserve(c, (void**)&c->predict_out, &c->predict_out_cap, (size_t)chunk_max * c->m * 4));
     const size_t xrow = (size_t)c->d * (c->storage == USL_F32 ? 4 : 2);
     for (int i0 = 0; i0 < b; i0 += chunk) {
         const int n = b - i0 < chunk ? b - i0 : chunk;
@@ -342,7 +346,8 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
         const uint32_t* gate = nullptr;
         if (loss_kind == 1 && usl_sparse_supported(c)) {
             USL_TRY(usl_sparse_compact(c, g, b, &gate));
-            c->nz_lists_of = g;
+            c->nz_lists_of = g;              // backward-weight below does not look a second time
+            c->nz_lists_tried = gate != nullptr;
         }
         usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);   // BCE gradients are dense
         c->nz_lists_of = nullptr;
@@ -388,6 +393,24 @@ extern "C" usl_status usl_redistribute_rows(usl_ctx* c, int32_t* idx, void* W, f
     c->csc_built_for = nullptr;
     c->slot_order_for = nullptr;
     return usl_launch_redistribute_rows(c, idx, W, m1, m2, per_row, seed, epoch);
+}
+
+extern "C" usl_status usl_check(usl_ctx* c) {
+    if (!c) return USL_EINVAL;
+    if (c->device < 0) return USL_OK;   // nothing was ever launched
+    USL_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->idx_print) {
+        uint32_t stale = 0;
+        USL_HIP(c, hipMemcpy(&stale, reinterpret_cast<uint32_t*>(c->idx_print) + 4, 4, hipMemcpyDeviceToHost));
+        if (stale) {
+            USL_HIP(c, hipMemset(reinterpret_cast<uint32_t*>(c->idx_print) + 4, 0, 4));
+            c->csc_built_for = nullptr;
+            c->slot_order_for = nullptr;
+            USL_FAIL(c, USL_ESTALE, "idx changed without usl_invalidate: a usl_backward_input call since the last "
+                                    "check ran on column lists of the old contents and filled grad_x with NaN");
+        }
+    }
+    return USL_OK;
 }
 
 extern "C" usl_status usl_validate_indices(usl_ctx* c, const int32_t* idx, int64_t* n_bad_host) {

@@ -32,6 +32,8 @@ struct usl_ctx {
     uint32_t* csc_order;      size_t csc_order_cap;   // [3][nwin*d] features of each window by falling list length; rank of each feature; list length by rank
     uint32_t* csc_slot;       // [m*k] flat slot j*k+t, grouped by (label window, feature)
     float* csc_w;             // [m*k] W of that slot (refreshed by every backward_input)
+    uint64_t* idx_print;      // [0] fingerprint of idx when the lists were built; word [2] (32 bits): 1 = a later call found idx changed
+    const int32_t* idx_to_check;  // idx whose fingerprint the next weight gather compares (NULL right after a build)
     int csc_win_labels;       // labels per window the lists were built with
     const int32_t* csc_built_for;  // idx pointer the lists were built from (NULL = stale)
     // bank-aware order in which a label's slots are visited by the LDS gathers (performance only)
@@ -51,7 +53,12 @@ struct usl_ctx {
     uint32_t* nz_state;       size_t nz_state_cap;   // [0] = 1: gradient is dense, lists abandoned; [16+i] = entries of instance i
     int32_t* nz_lab;          size_t nz_lab_cap;     // [max_b][m/32] label of an entry
     float* nz_val;            size_t nz_val_cap;     // [max_b][m/32] its gradient
-    const float* nz_lists_of; // g whose lists are current (only set inside usl_train_step), else NULL
+    const float* nz_lists_of; // g that has just been looked at (only set inside usl_train_step), else NULL
+    bool nz_lists_tried;      // ... and whether lists were built for it (else only the dense kernels run)
+    uint32_t* hint_host;      // pinned: [0] serial of the last finished look at a gradient sample, [1] 1 = it was dense
+    uint32_t* hint_dev;       // the same words as the device addresses them
+    uint32_t hint_seen, probe_serial;
+    int sparse_streak;        // looks in a row that found the sample sparse
 };
 
 #define USL_FAIL(ctx, code, ...)                                   \

@@ -6,16 +6,17 @@ CPU fallback: if the shared library is missing, importing this module raises.
 """
 import ctypes
 import os
+import weakref
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libusl.so")
 
-USL_OK, USL_EINVAL, USL_ESHAPE, USL_ENOMEM, USL_EHIP, USL_EUNSUPPORTED = range(6)
+USL_OK, USL_EINVAL, USL_ESHAPE, USL_ENOMEM, USL_EHIP, USL_EUNSUPPORTED, USL_ESTALE = range(7)
 USL_F32, USL_BF16 = 0, 1
-STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", "USL_EUNSUPPORTED"]
+STATUS_NAMES = ["USL_OK", "USL_EINVAL", "USL_ESHAPE", "USL_ENOMEM", "USL_EHIP", "USL_EUNSUPPORTED", "USL_ESTALE"]
 
 # every symbol include/usl.h declares
-SYMBOLS = ["usl_bce_loss_grad_noalloc", "usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
+SYMBOLS = ["usl_bce_loss_grad_noalloc", "usl_check", "usl_create", "usl_destroy", "usl_set_stream", "usl_invalidate", "usl_last_error",
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
            "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows", "usl_predict",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
@@ -35,6 +36,7 @@ _sig = {
     "usl_destroy": [_vp],
     "usl_set_stream": [_vp, _vp],
     "usl_invalidate": [_vp],
+    "usl_check": [_vp],
     "usl_init_indices": [_vp, _vp, _u64],
     "usl_forward": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_bce_loss_grad": [_vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32],
@@ -68,7 +70,7 @@ _lib.usl_version.restype = ctypes.c_char_p
 
 class UslError(RuntimeError):
     def __init__(self, status, message):
-        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < 6 else status, message))
+        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status, message))
         self.status = status
 
 
@@ -98,6 +100,7 @@ class Layer:
             self._h = _vp()
             raise UslError(s, "usl_create(m=%s, d=%s, k=%s, max_b=%s, storage=%s)" % (m, d, k, max_b, storage))
         self.m, self.d, self.k, self.max_b, self.storage = m, d, k, max_b, storage
+        self._idx_seen = None
 
     def close(self):
         if self._h and _lib is not None:      # _lib is gone when the interpreter is shutting down
@@ -116,10 +119,27 @@ class Layer:
     def invalidate(self):
         self._ck(_lib.usl_invalidate(self._h))
 
+    def check(self):
+        """Waits for the stream; raises UslError(USL_ESTALE) if a call ran on private views of an idx that changed."""
+        self._ck(_lib.usl_check(self._h))
+
+    def _same_idx(self, idx):
+        """The library keys its private views of the connectivity by the address of idx.  A different tensor
+        object at the same address (the caching allocator recycles addresses), or the same tensor after an
+        in-place torch operation, is new contents: tell the library so."""
+        if isinstance(idx, int) or idx is None:
+            return
+        seen = self._idx_seen
+        if seen is not None and (seen[0]() is not idx or seen[1] != idx._version):
+            _lib.usl_invalidate(self._h)
+        if seen is None or seen[0]() is not idx or seen[1] != idx._version:
+            self._idx_seen = (weakref.ref(idx), idx._version)
+
     def init_indices(self, idx, seed):
         self._ck(_lib.usl_init_indices(self._h, _ptr(idx), seed))
 
     def forward(self, x, idx, W, out, b):
+        self._same_idx(idx)
         self._ck(_lib.usl_forward(self._h, _ptr(x), _ptr(idx), _ptr(W), _ptr(out), b))
 
     def bce_loss_grad(self, out, tgt_off, tgt_lab, scale, g, loss, b):
@@ -150,6 +170,7 @@ class Layer:
         self._ck(_lib.usl_topk(self._h, _ptr(out), b, kk, _ptr(top_lab), _ptr(top_val)))
 
     def predict(self, x, idx, W, b, kk, top_lab, top_val):
+        self._same_idx(idx)
         self._ck(_lib.usl_predict(self._h, _ptr(x), _ptr(idx), _ptr(W), b, kk, _ptr(top_lab), _ptr(top_val)))
 
     def precision_hits(self, top_lab, tgt_off, tgt_lab, b, kk, hits):
@@ -157,9 +178,11 @@ class Layer:
                                          _ptr(hits)))
 
     def backward_weight(self, g, x, idx, grad_W, b):
+        self._same_idx(idx)
         self._ck(_lib.usl_backward_weight(self._h, _ptr(g), _ptr(x), _ptr(idx), _ptr(grad_W), b))
 
     def backward_input(self, g, idx, W, grad_x, b):
+        self._same_idx(idx)
         self._ck(_lib.usl_backward_input(self._h, _ptr(g), _ptr(idx), _ptr(W), _ptr(grad_x), b))
 
     def adam_step(self, W, grad_W, m1, m2, t, lr, beta1, beta2, eps):
@@ -168,6 +191,7 @@ class Layer:
 
     def train_step(self, x, idx, W, m1, m2, tgt_off, tgt_lab, loss_kind, scale, t, lr, beta1, beta2, eps,
                    g, grad_W, grad_x, loss, b):
+        self._same_idx(idx)
         self._ck(_lib.usl_train_step(self._h, _ptr(x), _ptr(idx), _ptr(W), _ptr(m1), _ptr(m2), _ptr(tgt_off),
                                      _ptr(tgt_lab), loss_kind, scale, t, lr, beta1, beta2, eps, _ptr(g),
                                      _ptr(grad_W), _ptr(grad_x) if grad_x is not None else None, _ptr(loss), b))

@@ -43,7 +43,8 @@ def test_create_rejects_bad_shapes(usl):
             usl.Layer(**kw)
         assert e.value.status == usl.USL_EINVAL
     for kw in [dict(m=4, d=4, k=5, max_b=1), dict(m=2 ** 31, d=8, k=1, max_b=1),
-               dict(m=2 ** 27, d=64, k=32, max_b=1), dict(m=4, d=2 ** 24 + 1, k=1, max_b=1)]:
+               dict(m=2 ** 27, d=64, k=32, max_b=1), dict(m=4, d=2 ** 24 + 1, k=1, max_b=1),
+               dict(m=4, d=4, k=2, max_b=65536)]:
         with pytest.raises(usl.UslError) as e:
             usl.Layer(**kw)
         assert e.value.status == usl.USL_ESHAPE

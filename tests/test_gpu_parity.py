@@ -108,6 +108,45 @@ def test_smaller_batch_than_max_and_reuse(usl, gu, orc):
     assert_close(gu.host(gx), orc.backward_input(g, idx2, W, cfg.d), 1e-4, "grad_x after invalidate")
 
 
+def test_new_idx_contents_at_an_old_address(usl, gu, orc):
+    """The private column lists are keyed by the address of idx.  (1) Through the binding, a new tensor that the
+    allocator places at the address of a freed one is recognised as new contents.  (2) Through the bare C ABI,
+    contents that change without usl_invalidate are caught by the fingerprint: grad_x is NaN, not numbers from
+    stale lists, usl_check reports USL_ESTALE, and the next call is right again."""
+    cfg = make("ragged_small")
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    W, g = wl.gen_W(cfg), wl.gen_g(cfg)
+    idx1 = wl.gen_idx(cfg)
+    idx2 = wl.gen_idx(wl.custom(m, d, k, b, index=77))
+    assert (idx1 != idx2).any()
+    L = usl.Layer(m, d, k, b)
+    d_W, d_g, gx = gu.dev(W), gu.dev(g), gu.empty((b, d))
+    d_idx = gu.dev(idx1)
+    addr = d_idx.data_ptr()
+    L.backward_input(d_g, d_idx, d_W, gx, b)
+    assert_close(gu.host(gx), orc.backward_input(g, idx1, W, d), 1e-4, "grad_x, first idx")
+    del d_idx
+    d_idx = gu.dev(idx2)                       # the caching allocator hands the freed block out again
+    if d_idx.data_ptr() == addr:
+        L.backward_input(d_g, d_idx, d_W, gx, b)
+        assert_close(gu.host(gx), orc.backward_input(g, idx2, W, d), 1e-4, "grad_x, new tensor at the old address")
+        L.check()
+    # the bare ABI: same address, contents replaced behind the library's back
+    d_idx.copy_(torch.from_numpy(idx1))
+    rc = usl._lib.usl_backward_input(L._h, d_g.data_ptr(), d_idx.data_ptr(), d_W.data_ptr(), gx.data_ptr(), b)
+    assert rc == usl.USL_OK
+    assert torch.isnan(gx).all()
+    with pytest.raises(usl.UslError) as e:
+        L.check()
+    assert e.value.status == usl.USL_ESTALE
+    L.check()                                   # reported once
+    rc = usl._lib.usl_backward_input(L._h, d_g.data_ptr(), d_idx.data_ptr(), d_W.data_ptr(), gx.data_ptr(), b)
+    assert rc == usl.USL_OK
+    assert_close(gu.host(gx), orc.backward_input(g, idx1, W, d), 1e-4, "grad_x after the check invalidated the lists")
+    L.check()
+    L.close()
+
+
 @pytest.mark.parametrize("name", ["tiny", "ragged_small", "odd_d", "big_blocks", "one"])
 def test_bce(usl, gu, orc, name):
     cfg = make(name)
@@ -169,9 +208,11 @@ SPARSE_G = [("tiny", "f32", 0.9), ("ragged_small", "f32", 0.99), ("k64", "f32", 
 
 
 @pytest.mark.parametrize("name,storage,zero_frac", SPARSE_G)
-def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_frac):
+def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_frac, monkeypatch):
     """Zero entries of g are skipped by the backward kernels; the sums must be those of the oracle,
     which skips nothing.  Patterns: iid zeros, whole instances zero, whole label ranges zero."""
+    # the lists of nonzeros are tried at once (left alone the library waits for two sparse gradients in a row)
+    monkeypatch.setenv("USL_TUNE_SPARSE", "always")
     cfg = make(name, storage)
     m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
     idx, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
@@ -213,6 +254,31 @@ def test_backward_with_mostly_zero_gradient(usl, gu, orc, name, storage, zero_fr
     assert_close(gu.host(gx), orc.backward_input(g2, idx, W, d), 1e-4, "grad_x dense after sparse")
     L.backward_weight(gu.dev(g2), d_x, d_idx, gW, b)
     assert_close(gu.host(gW), orc.backward_weight(g2, x, idx), 1e-5, "grad_W dense after sparse")
+
+
+def test_sparse_gradients_are_expected_after_two_in_a_row(usl, gu, orc):
+    """The library's own policy: sparse, sparse, sparse (lists by now), dense (gated dense kernels), dense, sparse.
+    Every call must be right whichever kernels did the work."""
+    cfg = make("big_one_group")
+    m, d, k, b = cfg.m, cfg.d, cfg.k, cfg.b
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    dense = wl.gen_g(cfg)
+    sparse = dense.copy()
+    sparse[wl.rng(cfg, 22).random(sparse.shape) < 0.998] = 0.0
+    L = usl.Layer(m, d, k, b)
+    d_idx, d_W, d_x = gu.dev(idx), gu.dev(W), gu.dev(x)
+    gW, gx = gu.empty((m, k)), gu.empty((b, d))
+    ref = {id(sparse): (orc.backward_weight(sparse, x, idx), orc.backward_input(sparse, idx, W, d)),
+           id(dense): (orc.backward_weight(dense, x, idx), orc.backward_input(dense, idx, W, d))}
+    for step, g in enumerate([sparse, sparse, sparse, sparse, dense, dense, sparse, sparse, sparse]):
+        d_g = gu.dev(g)
+        gW.fill_(float("nan")); gx.fill_(float("nan"))
+        L.backward_weight(d_g, d_x, d_idx, gW, b)
+        L.backward_input(d_g, d_idx, d_W, gx, b)
+        torch.cuda.synchronize()                      # the sample's verdict has reached the host before the next call
+        assert_close(gu.host(gW), ref[id(g)][0], 1e-5, "grad_W, call %d" % step)
+        assert_close(gu.host(gx), ref[id(g)][1], 1e-4, "grad_x, call %d" % step)
+    L.close()
 
 
 @pytest.mark.parametrize("storage", ["f32", "bf16"])

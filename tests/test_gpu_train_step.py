@@ -26,8 +26,10 @@ CASES = [
 
 
 @pytest.mark.parametrize("m,d,k,b,storage,loss_kind,with_gx,easy", CASES)
-def test_train_step(orc, m, d, k, b, storage, loss_kind, with_gx, easy):
+def test_train_step(orc, m, d, k, b, storage, loss_kind, with_gx, easy, monkeypatch):
     import gpu_util as gu
+    if easy:      # try the lists of nonzero gradients at once (left alone the library waits for two sparse steps in a row)
+        monkeypatch.setenv("USL_TUNE_SPARSE", "always")
     from paper_2306_03725_amd import usl
     cfg = wl.custom(m, d, k, b, storage=storage, positives=min(3, m), index=60 + CASES.index((m, d, k, b, storage, loss_kind, with_gx, easy)))
     print("train_step", m, d, k, b, storage, loss_kind, with_gx, easy, flush=True)
