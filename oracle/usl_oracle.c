@@ -38,56 +38,55 @@ static uint16_t to_bf16(float f) {
     return (uint16_t)(u >> 16);
 }
 
-/* Forward product (Section "Compressed indexing ...", Algorithm 1):
- * out[i][j] = sum_t x[i][idx[j][t]] * W[j][t]. */
+/* The layer is a dense m x d matrix A that is zero except at k places per row: A[j][col(j,t)] = val(j,t),
+ * t < k (Section 3.2, the uniform format).  The three products below are the dense-layer definitions
+ * restricted to those places; the accessors name the operands. */
+static int32_t col(const int32_t* idx, int32_t k, int64_t j, int32_t t) { return idx[j * k + t]; }
+static double val(const void* W, int32_t k, int64_t j, int32_t t, int storage) { return widen(W, j * k + t, storage); }
+static double act(const void* x, int32_t d, int32_t i, int32_t c, int storage) { return widen(x, (int64_t)i * d + c, storage); }
+
+/* Scores (Section 3.2, what Algorithm 1 computes): out = x A^T, i.e.
+ * out[i][j] = sum over the k connections of label j of val(j,t) * x[i][col(j,t)]. */
 void orc_forward(const void* x, const int32_t* idx, const void* W, float* out,
                  int64_t m, int32_t d, int32_t k, int32_t b, int storage) {
-    (void)d;
 #pragma omp parallel for schedule(static)
-    for (int32_t i = 0; i < b; ++i) {
+    for (int32_t i = 0; i < b; ++i)
         for (int64_t j = 0; j < m; ++j) {
-            double value = 0.0;
-            for (int32_t t = 0; t < k; ++t) {
-                int32_t source = idx[j * k + t];
-                value += widen(x, (int64_t)i * d + source, storage) * widen(W, j * k + t, storage);
-            }
-            out[(int64_t)i * m + j] = (float)value;
+            double score = 0.0;
+            for (int32_t t = 0; t < k; ++t) score += act(x, d, i, col(idx, k, j, t), storage) * val(W, k, j, t, storage);
+            out[(int64_t)i * m + j] = (float)score;
         }
-    }
 }
 
-/* Gradient with respect to the connection values (Algorithm 3, without the zero test,
- * which only skips terms that are exactly zero):
- * grad_W[j][t] = sum_i g[i][j] * x[i][idx[j][t]]. */
+/* Gradient of the connection values (Section 3.3, what Algorithm 3 computes; its test for a zero
+ * gradient only leaves out terms that are exactly zero): the dense gradient g^T x read at the k places
+ * of every row, grad_W[j][t] = sum over the batch of g[i][j] * x[i][col(j,t)]. */
 void orc_backward_weight(const float* g, const void* x, const int32_t* idx, float* grad_W,
                          int64_t m, int32_t d, int32_t k, int32_t b, int storage) {
 #pragma omp parallel for schedule(static)
-    for (int64_t j = 0; j < m; ++j) {
+    for (int64_t j = 0; j < m; ++j)
         for (int32_t t = 0; t < k; ++t) {
-            int32_t source = idx[j * k + t];
-            double result = 0.0;
-            for (int32_t i = 0; i < b; ++i)
-                result += widen(x, (int64_t)i * d + source, storage) * (double)g[(int64_t)i * m + j];
-            grad_W[j * k + t] = (float)result;
+            const int32_t c = col(idx, k, j, t);
+            double sum = 0.0;
+            for (int32_t i = 0; i < b; ++i) sum += act(x, d, i, c, storage) * (double)g[(int64_t)i * m + j];
+            grad_W[j * k + t] = (float)sum;
         }
-    }
 }
 
-/* Gradient with respect to the input features (Algorithm 2 with the atomic additions
- * done one after the other into a zeroed row, and without the zero test):
- * grad_x[i][c] = sum over connections (j,t) with idx[j][t]==c of W[j][t] * g[i][j]. */
+/* Gradient of the input features (Section 3.3, what Algorithm 2 computes with atomic additions; here
+ * the additions go one after the other into a zeroed row of doubles): grad_x = g A, i.e.
+ * grad_x[i][c] = sum over all connections (j,t) with col(j,t) == c of val(j,t) * g[i][j]. */
 void orc_backward_input(const float* g, const int32_t* idx, const void* W, float* grad_x,
                         int64_t m, int32_t d, int32_t k, int32_t b, int storage) {
 #pragma omp parallel for schedule(static)
     for (int32_t i = 0; i < b; ++i) {
-        double* row = (double*)calloc((size_t)d, sizeof(double));
+        double* sums = (double*)calloc((size_t)d, sizeof(double));
         for (int64_t j = 0; j < m; ++j) {
-            double o = (double)g[(int64_t)i * m + j];
-            for (int32_t t = 0; t < k; ++t)
-                row[idx[j * k + t]] += widen(W, j * k + t, storage) * o;
+            const double gij = (double)g[(int64_t)i * m + j];
+            for (int32_t t = 0; t < k; ++t) sums[col(idx, k, j, t)] += val(W, k, j, t, storage) * gij;
         }
-        for (int32_t c = 0; c < d; ++c) grad_x[(int64_t)i * d + c] = (float)row[c];
-        free(row);
+        for (int32_t c = 0; c < d; ++c) grad_x[(int64_t)i * d + c] = (float)sums[c];
+        free(sums);
     }
 }
 
