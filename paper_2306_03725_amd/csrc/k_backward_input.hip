@@ -274,7 +274,7 @@ k_gather_w(const TS* __restrict__ W, const uint32_t* __restrict__ slot, const ui
     for (; p < p1; p += STEP) wl[p] = usl_load_f32<TS>(W, (size_t)slot[p]);
 }
 
-// grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.x = tile, blockIdx.y = block of 32 features.
+// grad_x[i][c] = gxT[i/32][c][i%32] for i < b.  blockIdx.y = tile, blockIdx.x = block of 32 features.
 __global__ void __launch_bounds__(256)
 k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, int64_t d,
          const uint32_t* __restrict__ gate, const uint32_t* __restrict__ stale) {
@@ -282,11 +282,11 @@ k_untile(const float* __restrict__ gxT, float* __restrict__ grad_x, int64_t b, i
     if (gate && *gate == 0) return;
     const bool poison = *stale != 0;   // the lists were built from other contents of idx: no number is better than a wrong one
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const int64_t i0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
+    const int64_t i0 = (int64_t)blockIdx.y * 32, c0 = (int64_t)blockIdx.x * 32;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int64_t c = c0 + ty + 8 * q;
-        if (c < d) tile[ty + 8 * q][tx] = gxT[((size_t)blockIdx.x * d + c) * 32 + tx];
+        if (c < d) tile[ty + 8 * q][tx] = gxT[((size_t)blockIdx.y * d + c) * 32 + tx];
     }
     __syncthreads();
 #pragma unroll
@@ -540,16 +540,21 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
 
 }  // namespace
 
-// Lists for this idx, and the scratch a call with batch b needs; clears the nonzero-piece counter.
+// The batch goes through the gathers in groups of 256 instances (8 tiles, one per XCD): gT, its piece flags and
+// gxT are sized for one group, whatever the batch (at m = 3 million and b = 1024 that is 3 GB instead of 12).
+int usl_bwd_input_group_rows(void) { return 256; }
+
+// Lists for this idx, and the scratch of one group of instances.
 usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
+    (void)b;
     if (c->csc_built_for != idx || c->csc_win_labels != window_labels(c)) {
         USL_TRY(build_csc(c, idx));
         c->idx_to_check = nullptr;
     } else {   // same address as when the lists were built: the weight gather checks that the contents are the same
         c->idx_to_check = idx;
     }
-    (void)b;
-    const int ntile = (c->max_b + 31) / 32;   // sized once for the largest batch: a later call never has to grow them
+    const int rows = c->max_b < usl_bwd_input_group_rows() ? c->max_b : usl_bwd_input_group_rows();
+    const int ntile = (rows + 31) / 32;   // sized once, for the largest group any batch up to max_b brings
     USL_TRY(usl_reserve(c, (void**)&c->gT, &c->gT_cap, (size_t)ntile * c->m * 32 * 4));
     USL_TRY(usl_reserve(c, (void**)&c->gxT, &c->gxT_cap, (size_t)ntile * c->d * 32 * 4));
     USL_TRY(usl_reserve(c, (void**)&c->nz_flags, &c->nz_flags_cap, (size_t)ntile * c->m));
@@ -557,59 +562,64 @@ usl_status usl_bwd_input_prepare(usl_ctx* c, const int32_t* idx, int32_t b) {
         size_t cap = 0;
         USL_TRY(usl_reserve(c, (void**)&c->counter64, &cap, 64));
     }
+    return USL_OK;
+}
+
+// Weights in list order, once per call (every group of instances uses them).
+usl_status usl_bwd_input_gather_w(usl_ctx* c, const void* W, const uint32_t* gate) {
+    const int wl = c->csc_win_labels;
+    const int nwin = (int)((c->m + wl - 1) / wl);
+    const int bpw = nwin >= 8 ? 32 : 128;
+    const unsigned blocks = (unsigned)(nwin >= 8 ? (nwin + 7) / 8 * 8 : nwin) * bpw;
+    if (c->storage == USL_F32)
+        hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
+                           c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
+                           reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
+    else
+        hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
+                           c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
+                           reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
+    return usl_check_launch(c, "backward_input weights");
+}
+
+// Clears the count of nonzero pieces before a group's gT is produced.
+usl_status usl_bwd_input_begin_group(usl_ctx* c) {
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, usl_nz_cells(c), (size_t)1);
     return usl_check_launch(c, "backward_input scratch");
 }
 
-// The gathers, once gT, the piece flags and the sampled count of nonzero pieces are in place.
-// sampled_labels = how many labels the count covers (per tile).
-usl_status usl_bwd_input_run(usl_ctx* c, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels,
-                             const uint32_t* gate) {
+// The gathers of one group of rows instances, once its gT, piece flags and sampled count of nonzero pieces are in
+// place; grad_x_rows = the group's rows of grad_x.  sampled_labels = how many labels the count covers (per tile).
+usl_status usl_bwd_input_group(usl_ctx* c, float* grad_x_rows, int32_t rows, uint64_t sampled_labels,
+                               const uint32_t* gate) {
     const int wl = c->csc_win_labels;
     const int nwin = (int)((c->m + wl - 1) / wl);
-    const int ntile = (b + 31) / 32;
+    const int ntile = (rows + 31) / 32;   // at most 8: one per XCD, so that an XCD's L2 holds one window slice
     int kshift = -1;
     for (int q = 0; q < 31; ++q)
         if ((1 << q) == c->k) kshift = q;
-    {   // weights in list order
-        const int bpw = nwin >= 8 ? 32 : 128;
-        const unsigned blocks = (unsigned)(nwin >= 8 ? (nwin + 7) / 8 * 8 : nwin) * bpw;
-        if (c->storage == USL_F32)
-            hipLaunchKernelGGL(k_gather_w<float>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const float*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
-                               reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
-        else
-            hipLaunchKernelGGL(k_gather_w<uint16_t>, dim3(blocks), dim3(GW_NT), 0, c->stream, (const uint16_t*)W,
-                               c->csc_slot, c->csc_ptr, c->d, nwin, c->csc_w, bpw, gate,
-                               reinterpret_cast<const uint32_t*>(c->idx_to_check), (size_t)c->m * c->k, c->idx_print);
-    }
     // the flag lookup costs a dependent load per connection: worth it when under half the pieces are live
     const uint64_t cells = (uint64_t)ntile * (sampled_labels < (uint64_t)c->m ? sampled_labels : (uint64_t)c->m);
     const uint32_t sparse_below = (uint32_t)(cells / 2 > 0xFFFFFFFFull ? 0xFFFFFFFFull : cells / 2);
-    {
-        // 8 tiles per launch, one per XCD: with more, an XCD's L2 would have to hold several window slices
-        for (int t0 = 0; t0 < ntile; t0 += 8) {
-            const unsigned ntl = (unsigned)(ntile - t0 < 8 ? ntile - t0 : 8);
-            // too few (tile, 32 features) workgroups to fill the chip: a wavefront per feature instead
-            const bool split = (int64_t)ntl * ((c->d + 31) / 32) < 2 * (int64_t)c->num_cu;
-            dim3 grid(ntl, (unsigned)(split ? (c->d + 3) / 4 : (c->d + 31) / 32));
-            for (int w = 0; w < nwin; ++w) {
-                if (split)
-                    hipLaunchKernelGGL(k_bwd_input_window<8>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                                       c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
-                                       c->k, kshift, c->gxT, c->d, t0,
-                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
-                else
-                    hipLaunchKernelGGL(k_bwd_input_window<1>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
-                                       c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
-                                       c->k, kshift, c->gxT, c->d, t0,
-                                       w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
-            }
-        }
+    // too few (tile, 32 features) workgroups to fill the chip: a wavefront per feature instead
+    bool split = (int64_t)ntile * ((c->d + 31) / 32) < 2 * (int64_t)c->num_cu;
+    if ((c->d + 3) / 4 > 65535) split = false;   // the grid's second dimension
+    dim3 grid((unsigned)ntile, (unsigned)(split ? (c->d + 3) / 4 : (c->d + 31) / 32));
+    for (int w = 0; w < nwin; ++w) {
+        if (split)
+            hipLaunchKernelGGL(k_bwd_input_window<8>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                               c->k, kshift, c->gxT, c->d, 0,
+                               w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
+        else
+            hipLaunchKernelGGL(k_bwd_input_window<1>, grid, dim3(256), 0, c->stream, c->gT, c->csc_w,
+                               c->csc_ptr + (size_t)w * c->d, c->csc_order + (size_t)w * c->d, c->csc_slot,
+                               c->k, kshift, c->gxT, c->d, 0,
+                               w > 0 ? 1 : 0, c->nz_flags, c->m, usl_nz_cells(c), sparse_below, gate);
     }
     {
-        dim3 grid((unsigned)ntile, (unsigned)((c->d + 31) / 32));
-        hipLaunchKernelGGL(k_untile, grid, dim3(256), 0, c->stream, c->gxT, grad_x, (int64_t)b, (int64_t)c->d, gate,
+        dim3 grid2((unsigned)((c->d + 31) / 32), (unsigned)ntile);
+        hipLaunchKernelGGL(k_untile, grid2, dim3(256), 0, c->stream, c->gxT, grad_x_rows, (int64_t)rows, (int64_t)c->d, gate,
                            reinterpret_cast<const uint32_t*>(c->idx_print) + 4);
     }
     return usl_check_launch(c, "backward_input");
@@ -625,10 +635,17 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
         USL_TRY(usl_sparse_compact(c, g, b, &gate));
         if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
     }
-    {   // gT = g transposed tile by tile, with the zero flags of every (label, tile) piece
-        dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((b + 31) / 32));
-        hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g, c->gT, (int64_t)b, c->m,
-                           c->nz_flags, usl_nz_cells(c), gate);
+    USL_TRY(usl_bwd_input_gather_w(c, W, gate));
+    const int G = usl_bwd_input_group_rows();
+    for (int i0 = 0; i0 < b; i0 += G) {
+        const int rows = b - i0 < G ? b - i0 : G;
+        USL_TRY(usl_bwd_input_begin_group(c));
+        {   // gT = the group's rows of g transposed tile by tile, with the zero flags of every (label, tile) piece
+            dim3 grid((unsigned)((c->m + 31) / 32), (unsigned)((rows + 31) / 32));
+            hipLaunchKernelGGL(k_transpose_g, grid, dim3(256), 0, c->stream, g + (size_t)i0 * c->m, c->gT, (int64_t)rows,
+                               c->m, c->nz_flags, usl_nz_cells(c), gate);
+        }
+        USL_TRY(usl_bwd_input_group(c, grad_x + (size_t)i0 * c->d, rows, (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32, gate));
     }
-    return usl_bwd_input_run(c, W, grad_x, b, (uint64_t)(((c->m + 31) / 32 + 63) / 64) * 32, gate);
+    return USL_OK;
 }

@@ -113,13 +113,13 @@ template <bool VEC, int LOSS>
 __global__ void __launch_bounds__(256)
 k_loss_tiles(float* zg, const int64_t* __restrict__ tgt_off, const int32_t* __restrict__ tgt_lab, float scale,
              double* __restrict__ partials, int64_t m, int b, float* __restrict__ gT,
-             uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells) {
+             uint8_t* __restrict__ nzf, uint32_t* __restrict__ nz_cells, int row0) {
     __shared__ float tile[32][LT_TL + 1];
     __shared__ uint32_t ybits[32][LT_TL / 32];
     __shared__ double red[4];
     __shared__ uint32_t block_cells;
     const int tid = threadIdx.x;
-    const int i0 = blockIdx.y * 32;
+    const int i0 = row0 + blockIdx.y * 32;   // gT and the flags are indexed by the tile within the group (blockIdx.y)
     const int64_t j0 = (int64_t)blockIdx.x * LT_TL;
     const int nl = (int)min((int64_t)LT_TL, m - j0);
     if (tid < 32 * (LT_TL / 32)) (&ybits[0][0])[tid] = 0u;
@@ -186,7 +186,7 @@ k_loss_tiles(float* zg, const int64_t* __restrict__ tgt_off, const int32_t* __re
     if ((tid & 63) == 0) red[tid >> 6] = v;
     __syncthreads();
     if (tid == 0) {
-        partials[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+        partials[(size_t)(row0 / 32 + blockIdx.y) * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
         if ((blockIdx.x % LT_SAMPLE) == 0 && block_cells) atomicAdd(nz_cells, block_cells);
     }
 }
@@ -340,22 +340,25 @@ usl_status usl_launch_loss_noalloc(usl_ctx* c, int loss_kind, const float* out, 
 
 usl_status usl_launch_loss_tiles(usl_ctx* c, int loss_kind, float* zg, const int64_t* tgt_off,
                                  const int32_t* tgt_lab, float scale, float* loss, int32_t b,
-                                 uint64_t* sampled_labels) {
+                                 uint64_t* sampled_labels, int32_t row0, int32_t rows) {
     const int64_t nlb = (c->m + LT_TL - 1) / LT_TL;
-    const int ntile = (b + 31) / 32;
-    const size_t nblk = (size_t)nlb * ntile;
+    const int ntile = (rows + 31) / 32;
     USL_TRY(usl_reserve_loss_partials(c));
     const bool vec = (c->m % 4 == 0) && ((uintptr_t)zg % 16 == 0);
     dim3 grid((unsigned)nlb, (unsigned)ntile);
+    const int b_end = row0 + rows;   // instances at and past it belong to a later group (or do not exist)
 #define USL_LOSS(VEC, KIND)                                                                              \
     hipLaunchKernelGGL((k_loss_tiles<VEC, KIND>), grid, dim3(256), 0, c->stream, zg, tgt_off, tgt_lab,   \
-                       scale, c->bce_partials, c->m, (int)b, c->gT, c->nz_flags, usl_nz_cells(c))
+                       scale, c->bce_partials, c->m, b_end, c->gT, c->nz_flags, usl_nz_cells(c), (int)row0)
     if (loss_kind == LOSS_BCE) { if (vec) USL_LOSS(true, LOSS_BCE); else USL_LOSS(false, LOSS_BCE); }
     else                       { if (vec) USL_LOSS(true, LOSS_SQH); else USL_LOSS(false, LOSS_SQH); }
 #undef USL_LOSS
     USL_TRY(usl_check_launch(c, "loss (tiles)"));
     *sampled_labels = (uint64_t)((nlb + LT_SAMPLE - 1) / LT_SAMPLE) * LT_TL;
-    hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, c->bce_partials, nblk, scale, loss);
+    if (b_end >= b) {   // the last group: every tile of the batch has left its sums
+        const size_t nblk = (size_t)nlb * (size_t)((b + 31) / 32);
+        hipLaunchKernelGGL(k_bce_finish, dim3(1), dim3(1024), 0, c->stream, c->bce_partials, nblk, scale, loss);
+    }
     return usl_check_launch(c, "loss_finish");
 }
 

@@ -338,22 +338,40 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
     USL_TRY(usl_prepare_device(c));
     USL_TRY(usl_launch_forward(c, x, idx, W, g, b));
     if (grad_x) {
-        uint64_t sampled = 0;
-        USL_TRY(usl_bwd_input_prepare(c, idx, b));
-        USL_TRY(usl_launch_loss_tiles(c, loss_kind, g, tgt_off, tgt_lab, scale, loss, b, &sampled));
-        // squared hinge: the gradient of a trained layer is almost all zeros (Section 3.3); its nonzeros are listed
-        // once and both backward products try the lists first (the device decides, see k_sparse_grad.hip)
-        const uint32_t* gate = nullptr;
-        if (loss_kind == 1 && usl_sparse_supported(c)) {
-            USL_TRY(usl_sparse_compact(c, g, b, &gate));
-            c->nz_lists_of = g;              // backward-weight below does not look a second time
-            c->nz_lists_tried = gate != nullptr;
+        // The loss writes the gradient in place and, group of 256 instances by group, as the tile-major pieces the
+        // input-gradient gathers read; the gathers of a group run before the next group's pieces replace them.
+        // Squared hinge: the gradient of a trained layer is almost all zeros (Section 3.3); when the context expects
+        // that, its nonzeros are listed once and both backward products try the lists first (k_sparse_grad.hip).
+        const int G = usl_bwd_input_group_rows();
+        const bool lists = loss_kind == 1 && usl_sparse_supported(c);
+        if (lists && b > G) {
+            // squared hinge on a batch of several groups: the look at the whole gradient needs all of it, so the
+            // stages run as the separate calls do
+            USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
+            USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, false));
+            USL_TRY(usl_launch_backward_input(c, g, idx, W, grad_x, b));
+        } else {
+            USL_TRY(usl_bwd_input_prepare(c, idx, b));
+            const uint32_t* gate = nullptr;
+            uint64_t sampled = 0;
+            if (!lists) USL_TRY(usl_bwd_input_gather_w(c, W, nullptr));
+            for (int i0 = 0; i0 < b; i0 += G) {
+                const int rows = b - i0 < G ? b - i0 : G;
+                USL_TRY(usl_bwd_input_begin_group(c));
+                USL_TRY(usl_launch_loss_tiles(c, loss_kind, g, tgt_off, tgt_lab, scale, loss, b, &sampled, i0, rows));
+                if (lists) {                        // one group: its pieces stay valid while g is looked at
+                    USL_TRY(usl_sparse_compact(c, g, b, &gate));
+                    c->nz_lists_of = g;             // backward-weight below does not look a second time
+                    c->nz_lists_tried = gate != nullptr;
+                    if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
+                    USL_TRY(usl_bwd_input_gather_w(c, W, gate));
+                }
+                USL_TRY(usl_bwd_input_group(c, grad_x + (size_t)i0 * c->d, rows, sampled, gate));
+            }
+            const usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);   // BCE gradients are dense
+            c->nz_lists_of = nullptr;
+            USL_TRY(s);
         }
-        usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);   // BCE gradients are dense
-        c->nz_lists_of = nullptr;
-        USL_TRY(s);
-        if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
-        USL_TRY(usl_bwd_input_run(c, W, grad_x, b, sampled, gate));
     } else {
         USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
         USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0));   // BCE gradients are dense

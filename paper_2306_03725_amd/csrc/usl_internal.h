@@ -103,17 +103,23 @@ bool usl_sparse_supported(const usl_ctx* ctx);
 usl_status usl_sparse_compact(usl_ctx* ctx, const float* g, int32_t b, const uint32_t** gate);
 usl_status usl_sparse_backward_weight(usl_ctx* ctx, const void* x, const int32_t* idx, float* grad_W, int32_t b);
 usl_status usl_sparse_backward_input(usl_ctx* ctx, const int32_t* idx, const void* W, float* grad_x, int32_t b);
-// backward_input in two halves, for callers that produce gT / nz_flags / the nonzero count themselves
+// backward_input in pieces, for callers that produce gT / nz_flags / the nonzero count themselves, one group of
+// at most usl_bwd_input_group_rows() instances at a time
+int usl_bwd_input_group_rows(void);
 usl_status usl_bwd_input_prepare(usl_ctx* ctx, const int32_t* idx, int32_t b);
-usl_status usl_bwd_input_run(usl_ctx* ctx, const void* W, float* grad_x, int32_t b, uint64_t sampled_labels,
-                             const uint32_t* gate = nullptr);
+usl_status usl_bwd_input_gather_w(usl_ctx* ctx, const void* W, const uint32_t* gate);
+usl_status usl_bwd_input_begin_group(usl_ctx* ctx);
+usl_status usl_bwd_input_group(usl_ctx* ctx, float* grad_x_rows, int32_t rows, uint64_t sampled_labels,
+                               const uint32_t* gate);
 static inline uint32_t* usl_nz_cells(usl_ctx* c) { return reinterpret_cast<uint32_t*>(c->counter64) + 4; }
 // Loss and gradient in place on zg[b][m], which also leaves the gradient in c->gT (tile-major) with
 // its piece flags and sampled nonzero count (usl_bwd_input_prepare must have run); *sampled_labels
 // receives the number of labels the count covers.
+// One call per group of instances [row0, row0 + rows) (row0 a multiple of 32); the call for the last group also
+// sums the loss over the whole batch of b instances.
 usl_status usl_launch_loss_tiles(usl_ctx* ctx, int loss_kind, float* zg, const int64_t* tgt_off,
                                  const int32_t* tgt_lab, float scale, float* loss, int32_t b,
-                                 uint64_t* sampled_labels);
+                                 uint64_t* sampled_labels, int32_t row0, int32_t rows);
 // loss_kind: 0 = binary cross-entropy, 1 = squared hinge
 usl_status usl_launch_loss(usl_ctx* ctx, int loss_kind, const float* out, const int64_t* tgt_off,
                            const int32_t* tgt_lab, float scale, float* g, float* loss, int32_t b);
