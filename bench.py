@@ -366,6 +366,25 @@ def main():
                     "nonzero_share": round(nz, 5),
                     "backward_weight_ms": round(timed(lambda: L.backward_weight(gbuf, x0, idx, gW, b)), 4),
                     "backward_input_ms": round(timed(lambda: L.backward_input(gbuf, idx, W, gx, b)), 4)}
+            if cfg.storage == "f32":
+                # The whole step under the squared hinge loss on a layer whose easy negatives are already separated
+                # (stand-in for a trained model: all weights negative and large on non-negative activations, so
+                # every score of a negative lies below -1 and only the positives keep a gradient).
+                W_easy = -(W.abs() * 8.0 + 0.5)
+                m1e, m2e = torch.zeros_like(W_easy), torch.zeros_like(W_easy)
+                hp = wl.ADAM
+                tt = [0]
+
+                def easy_step():
+                    tt[0] += 1
+                    L.train_step(x0, idx, W_easy, m1e, m2e, off0, lab0, 1, scale, tt[0], hp["lr"], hp["beta1"],
+                                 hp["beta2"], hp["eps"], gbuf, gW, gx, loss, b)
+                sweep["train_step_easy_negatives"] = {
+                    "ms_per_step": round(timed(easy_step, 10), 4),
+                    "nonzero_share": round(float((gbuf != 0).float().mean().item()), 6),
+                    "note": "usl_train_step with loss_kind = 1 (squared hinge), no redistribution; the step with "
+                            "binary cross-entropy on the same shapes is ms_per_step above"}
+                del W_easy, m1e, m2e
             res["sqh_zero_skipping"] = sweep
             del gbuf
         except Exception as exc:   # the headline line must survive a failure of an appended leg

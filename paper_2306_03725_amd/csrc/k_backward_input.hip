@@ -632,7 +632,8 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
     // two paths does the work is decided on the device (gate), both are enqueued
     const uint32_t* gate = nullptr;
     if (usl_sparse_supported(c)) {
-        USL_TRY(usl_sparse_compact(c, g, b, &gate));
+        if (c->nz_lists_of == g) gate = c->nz_lists_tried ? c->nz_state : nullptr;   // usl_train_step has looked already
+        else USL_TRY(usl_sparse_compact(c, g, b, &gate));
         if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
     }
     USL_TRY(usl_bwd_input_gather_w(c, W, gate));

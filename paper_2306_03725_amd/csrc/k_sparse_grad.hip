@@ -197,6 +197,25 @@ bool usl_sparse_supported(const usl_ctx* c) {
     return c->m >= 65536 && (size_t)c->max_b * list_capacity(c) * 8 <= ((size_t)4 << 30);
 }
 
+// Does the context expect a gradient that is almost all zeros?  Reads, without waiting, what the looks of
+// earlier calls reported (whichever of them have finished by now).
+bool usl_sparse_expected(usl_ctx* c) {
+    if (c->hint_host) {
+        const volatile uint32_t* h = c->hint_host;
+        const uint32_t serial = h[0], dense = h[1];
+        if (serial != c->hint_seen) {
+            c->hint_seen = serial;
+            c->sparse_streak = dense ? 0 : c->sparse_streak + 1;
+        }
+    }
+    bool expected = c->sparse_streak >= 2;
+    if (const char* e = getenv("USL_TUNE_SPARSE")) {
+        if (!strcmp(e, "always")) expected = true;
+        else if (!strcmp(e, "never")) expected = false;
+    }
+    return expected;
+}
+
 // Looks at g[b][m] and, if the context has reason to expect a gradient that is almost all zeros, builds the
 // lists of its nonzeros.  Every call enqueues the sample look (a few microseconds), whose verdict reaches the host
 // through two pinned words that the NEXT calls read without waiting: after two such looks in a row that found
@@ -215,19 +234,7 @@ usl_status usl_sparse_compact(usl_ctx* c, const float* g, int32_t b, const uint3
         USL_HIP(c, hipHostGetDevicePointer((void**)&c->hint_dev, c->hint_host, 0));
     }
     USL_TRY(usl_reserve(c, (void**)&c->nz_state, &c->nz_state_cap, ((size_t)c->max_b + 16) * 4));
-    {   // what earlier looks found (whichever of them have finished by now)
-        const volatile uint32_t* h = c->hint_host;
-        const uint32_t serial = h[0], dense = h[1];
-        if (serial != c->hint_seen) {
-            c->hint_seen = serial;
-            c->sparse_streak = dense ? 0 : c->sparse_streak + 1;
-        }
-    }
-    bool try_lists = c->sparse_streak >= 2;
-    if (const char* e = getenv("USL_TUNE_SPARSE")) {
-        if (!strcmp(e, "always")) try_lists = true;
-        else if (!strcmp(e, "never")) try_lists = false;
-    }
+    const bool try_lists = usl_sparse_expected(c);
     hipLaunchKernelGGL(k_zero_state, dim3(1), dim3(256), 0, c->stream, c->nz_state, (size_t)b + 16);
     hipLaunchKernelGGL(k_probe_density, dim3((unsigned)b), dim3(256), 0, c->stream, g, c->m, c->nz_state, c->hint_dev,
                        ++c->probe_serial);

@@ -344,12 +344,19 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
         // that, its nonzeros are listed once and both backward products try the lists first (k_sparse_grad.hip).
         const int G = usl_bwd_input_group_rows();
         const bool lists = loss_kind == 1 && usl_sparse_supported(c);
-        if (lists && b > G) {
-            // squared hinge on a batch of several groups: the look at the whole gradient needs all of it, so the
-            // stages run as the separate calls do
+        if (lists && (b > G || usl_sparse_expected(c))) {
+            // squared hinge where a gradient of almost only zeros is expected (or the batch has several groups, and
+            // the look at the gradient needs all of it): the loss writes the gradient row-major only, its nonzeros are
+            // listed once, and both backward products use the lists (the dense kernels stand by behind the gate)
             USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
-            USL_TRY(usl_launch_backward_weight(c, g, x, idx, grad_W, b, false));
-            USL_TRY(usl_launch_backward_input(c, g, idx, W, grad_x, b));
+            const uint32_t* gate = nullptr;
+            USL_TRY(usl_sparse_compact(c, g, b, &gate));
+            c->nz_lists_of = g;
+            c->nz_lists_tried = gate != nullptr;
+            usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, false);
+            if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
+            c->nz_lists_of = nullptr;
+            USL_TRY(s);
         } else {
             USL_TRY(usl_bwd_input_prepare(c, idx, b));
             const uint32_t* gate = nullptr;

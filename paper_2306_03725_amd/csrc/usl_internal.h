@@ -100,6 +100,7 @@ usl_status usl_launch_backward_input(usl_ctx* ctx, const float* g, const int32_t
 // finds g dense); *gate is a device word, 0 = the lists stand and the sparse kernels do the work, 1 = the dense
 // kernels have to.  Dense kernels that are handed the gate leave at once when it reads 0.
 bool usl_sparse_supported(const usl_ctx* ctx);
+bool usl_sparse_expected(usl_ctx* ctx);
 usl_status usl_sparse_compact(usl_ctx* ctx, const float* g, int32_t b, const uint32_t** gate);
 usl_status usl_sparse_backward_weight(usl_ctx* ctx, const void* x, const int32_t* idx, float* grad_W, int32_t b);
 usl_status usl_sparse_backward_input(usl_ctx* ctx, const int32_t* idx, const void* W, float* grad_x, int32_t b);
