@@ -19,17 +19,21 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 
-# HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the
-# same counters read for a plain copy of known size); summary and commands in
-# profiles/train_step_large_f32_hbm_bytes.txt.  Only the workload it was measured on has an entry.
+# HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the same
+# counter reads for a plain copy of known size); summaries and commands in profiles/train_step_<workload>_*_hbm_bytes.txt.
+# They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
+# profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 5527399 * 1024, "forward": 903295 * 1024, "backward_weight": 918642 * 1024},
+    "large": {"backward_input": 5671852441, "forward": 924948889, "backward_weight": 940677529},
+    "large_wide": {"backward_input": 31748259840, "forward": 2478204518, "backward_weight": 2652058419},
+    "stress": {"backward_input": 162917987123, "forward": 26036876083, "backward_weight": 26131772211},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
     "bce": "k_bce + k_bce_finish",
     "backward_weight": "k_backward_weight (1 launch)",
-    "backward_input": "k_gather_w + k_transpose_g + one k_bwd_input_window per label window + k_untile",
+    "backward_input": "a look at a sample of g, k_gather_w, then per group of 256 instances k_transpose_g + one "
+                      "k_bwd_input_window per window of 24576 labels + k_untile",
     "adam": "k_adam (1 launch)",
 }
 
@@ -47,6 +51,14 @@ def algorithmic_bytes(cfg):
     }
     per["step"] = sum(per.values())
     return per
+
+
+def launches_in_call(cfg, call):
+    """Kernel launches behind one call (the HIP-event time of the call covers all of them)."""
+    if call != "backward_input":
+        return 2 if call == "bce" else 1
+    groups = -(-cfg.b // 256)
+    return 3 + groups * (1 + -(-cfg.m // 24576) + 1 + 1)
 
 
 def cpu_baseline(cfg, budget_s=12.0, max_reps=5):
@@ -201,6 +213,12 @@ def workload_summary(name, steps, warmup, torch, usl, wl):
            "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
            "call_frac_of_peak": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) for c in CALLS[:5]},
            "bad_rows": B.L.validate_indices(B.idx), "redistributions": B.epoch}
+    dom = max(CALLS[:5], key=lambda c: call_ms[c] or 0.0)
+    res["roofline"] = {"bound": "hbm", "kernel": "usl_" + dom, "ms_per_launch": round(call_ms[dom], 4),
+                       "launches_in_call": launches_in_call(cfg, dom), "algorithmic_bytes": ab[dom],
+                       "achieved": round(ab[dom] / (call_ms[dom] * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                       "frac": round(ab[dom] / (call_ms[dom] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                       "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom)}
     B.close()
     return res
 
@@ -283,10 +301,13 @@ def main():
     roof = {"bound": "hbm", "kernel": "usl_%s: %s" % (dom, KERNELS_OF_CALL[dom]),
             "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
-            "ms_per_launch": round(call_ms[dom], 4), "algorithmic_bytes": ab[dom],
+            "ms_per_launch": round(call_ms[dom], 4), "launches_in_call": launches_in_call(cfg, dom),
+            "algorithmic_bytes": ab[dom],
             "traffic": traffic,
-            "note": "dominant call of the step; achieved = algorithmic bytes / HIP-event time of the call; "
-                    "traffic = HBM bytes per call from rocprofv3 counters (profiles/), measured offline"}
+            "note": "dominant call of the step (usl_train_step runs the same kernels); achieved = algorithmic bytes "
+                    "of the call / HIP-event time of the call on the launch stream, which covers launches_in_call "
+                    "kernel launches (per-kernel durations: profiles/train_step_*_kernel_trace.txt); traffic = HBM "
+                    "bytes per call from rocprofv3 counters (profiles/train_step_*_hbm_bytes.txt), measured offline"}
     step_gbps = ab["step"] / (ms_per_step * 1e-3) / 1e9
     res = {
         "metric": "sparse_layer_train_steps_per_s", "value": round(steps_per_s, 2), "unit": "steps/s",
