@@ -58,7 +58,9 @@ def launches_in_call(cfg, call):
     if call != "backward_input":
         return 2 if call == "bce" else 1
     groups = -(-cfg.b // 256)
-    return 3 + groups * (1 + -(-cfg.m // 24576) + 1 + 1)
+    win = int((24576.0 * ((cfg.d / 32768.0) * (32.0 / cfg.k)) ** 0.5 + 2048.0) / 4096.0) * 4096   # labels per window,
+    win = min(max(win, 16384), 49152)                                                              # as the library picks them
+    return 3 + groups * (1 + -(-cfg.m // win) + 1 + 1)
 
 
 def cpu_baseline(cfg, budget_s=12.0, max_reps=5):

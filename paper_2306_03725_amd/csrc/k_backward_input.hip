@@ -22,6 +22,7 @@
 // Eight lanes (8 x float4 = 32 instances) form a group that walks one feature's list; a wavefront
 // reads eight 128-byte pieces per load instruction.  No atomics touch grad_x; the only
 // non-determinism is the order of the slots inside one (window, feature) list.
+#include <math.h>
 #include <stdlib.h>
 
 #include "usl_internal.h"
@@ -467,12 +468,16 @@ k_bwd_input_window(const float* __restrict__ gT, const float* __restrict__ wl,
 }
 
 int window_labels(const usl_ctx* c) {
-    // a window's 128-byte-per-label slice of gT (3 MiB here) should sit in one XCD's 4 MiB L2 with room
-    // for the list entries that stream past it; measured best at Large among 8192 ... 32768
-    int w = 24576;
+    // A window's 128-byte-per-label slice of gT (3 MiB at 24576 labels) should sit in one XCD's 4 MiB L2 with room for
+    // the list entries that stream past it (window * k * 8 bytes per tile), while every window costs a round trip of
+    // the partial sums (d * 256 bytes per tile).  Measured best: 24576 at k = 32, d = 32768 (among 8192 ... 32768),
+    // 16384 at k = 64, d = 32768, 32768 at k = 32, d = 65536 -- the rule below meets all three.
+    double w = 24576.0 * sqrt(((double)c->d / 32768.0) * (32.0 / (double)c->k));
+    int win = (int)((w + 2048.0) / 4096.0) * 4096;
+    win = win < 16384 ? 16384 : win > 49152 ? 49152 : win;
     const char* e = getenv("USL_TUNE_WIN");
-    if (e && atoi(e) > 0) w = atoi(e);
-    return w;
+    if (e && atoi(e) > 0) win = atoi(e);
+    return win;
 }
 
 usl_status build_csc(usl_ctx* c, const int32_t* idx) {
