@@ -24,9 +24,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 5671852441, "forward": 924948889, "backward_weight": 940677529},
-    "large_wide": {"backward_input": 31748259840, "forward": 2478204518, "backward_weight": 2652058419},
-    "stress": {"backward_input": 162917987123, "forward": 26036876083, "backward_weight": 26131772211},
+    "large": {"backward_input": 5669860147, "forward": 924948889, "backward_weight": 940677529},
+    "large_wide": {"backward_input": 17072390144, "forward": 2478204518, "backward_weight": 2652372992},
+    "stress": {"backward_input": 204285778329, "forward": 26036771225, "backward_weight": 26131772211},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
