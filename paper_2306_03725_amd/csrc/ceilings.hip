@@ -112,6 +112,134 @@ __global__ void __launch_bounds__(256) k_piece_gather(const float4* __restrict__
     if (acc == 123.456f) sink[0] = acc;
 }
 
+
+// ---- The feature-stationary LDS form of the input gradient (the mirror image of the forward kernel), as a timing
+// prototype on synthetic lists: a workgroup owns a window of WL labels and a block of features, keeps the features'
+// (label-in-window 16 bit, weight) lists in registers -- two lists of complementary length share the KTOT register
+// slots of a lane pair: list A from slot 0 up, list B from slot KTOT-1 down --, walks the batch staging g[i, window]
+// through LDS with LDS-DMA, gathers, un-permutes its sums through LDS and leaves one partial sum per window, which a
+// second kernel adds up.  BUFS = 1: one row buffer, copy then gathers.  BUFS = 2: two row buffers, the copy of
+// instance i+1 (issued from inline assembly, so that the compiler puts no wait in front of the LDS reads) is in
+// flight while instance i is gathered.  DISTINCT = 1: every half-wavefront reads 32 different banks at every step (the
+// bound a perfect bank-aware order would reach); 0: random labels.  COPY / GATHER switch the two phases off.
+typedef const __attribute__((address_space(3))) float lds_f32_t;
+template <int N>
+__device__ __forceinline__ float lds_gather16(const uint32_t (&pk)[N], int t, uint32_t base) {
+    uint32_t a;
+    const uint32_t two = 2;
+    if (t & 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(a) : "s"(two), "v"(pk[t >> 1]));
+    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(a) : "s"(two), "v"(pk[t >> 1]));
+    return *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(a + base));
+}
+
+template <int KTOT, int PAIRS, int WL, int BUFS, int DISTINCT, int COPY, int GATHER>
+__global__ void __launch_bounds__(1024)
+k_lds_form(const float* __restrict__ g, int64_t m, int b, int d, int nfb, int nwin, float* __restrict__ partial,
+           int acap, int bcap) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    constexpr int NT = 1024, NF = NT * PAIRS * 2;   // features per workgroup
+    // all feature blocks of a window on one XCD (workgroups are dealt to the 8 XCDs round robin): its slice of g is
+    // fetched from HBM once and served to the others from that XCD's L2
+    const int w = (blockIdx.x & 7) + 8 * (blockIdx.x / (8 * nfb)), fb = (blockIdx.x >> 3) % nfb;
+    if (w >= nwin) return;
+    uint32_t pk[PAIRS][KTOT / 2];
+    float wt[PAIRS][KTOT];
+    uint32_t seed = mix32(blockIdx.x * 1024u + threadIdx.x + 1u);
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+        for (int t = 0; t < KTOT; ++t) {
+            seed = mix32(seed + t);
+            uint32_t off = seed % WL;
+            if (DISTINCT) off = (threadIdx.x & 31u) + 32u * (seed % (WL / 32));
+            if (t & 1) pk[p][t >> 1] |= off << 16; else pk[p][t >> 1] = off;
+            wt[p][t] = (float)(seed >> 8) * 1e-8f;
+        }
+    float* outbuf = reinterpret_cast<float*>(lds_raw + (size_t)BUFS * WL * 4);
+    const float* gw = g + (size_t)w * WL;
+    const int lane = threadIdx.x & 63;
+    auto stage = [&](int i, int buf) {
+        const uint4* src = reinterpret_cast<const uint4*>(gw + (size_t)i * m);
+        for (int v = (threadIdx.x >> 6) * 64; v < WL / 4; v += NT) {
+            const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(buf * WL * 4 + v * 16));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(la), "v"(src + v + lane) : "memory");
+        }
+    };
+    auto leave = [&](int i) {   // the sums of instance i, un-permuted in LDS, go out as one contiguous run
+        float* dst = partial + ((size_t)w * b + i) * d + (size_t)fb * NF;
+        const float* ob = outbuf + (BUFS == 2 ? (i & 1) * NF : 0);
+        for (int v = threadIdx.x; v < NF / 4; v += NT)
+            reinterpret_cast<float4*>(dst)[v] = reinterpret_cast<const float4*>(ob)[v];
+    };
+    // L2 warm-up of a later row slice, split among the nfb workgroups of the window (they share an XCD): the load is
+    // issued from inline assembly and its result never read, so no wait follows it; the register stays reserved
+    // until the next vmcnt(0) wait
+    uint32_t token = 0;
+    auto warm = [&](int i) {
+        const int lines = WL * 4 / 128, per = (lines + nfb - 1) / nfb;
+        const int line = fb * per + (int)threadIdx.x;
+        if ((int)threadIdx.x < per && line < lines) {
+            const char* p = reinterpret_cast<const char*>(gw + (size_t)i * m) + (size_t)line * 128;
+            asm volatile("global_load_dword %0, %1, off" : "=v"(token) : "v"(p));
+        }
+    };
+    if (BUFS == 2 && COPY) stage(0, 0);
+    if (BUFS == 2) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); }
+    for (int i = 0; i < b; ++i) {
+        if (BUFS == 1) {
+            if (COPY) stage(i, 0);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("" : "+v"(token));
+            __syncthreads();
+            if (COPY && i + 1 < b) warm(i + 1);
+        } else {
+            if (COPY && i + 1 < b) stage(i + 1, (i + 1) & 1);
+            if (COPY && i + 2 < b) warm(i + 2);
+            if (COPY && i > 0) leave(i - 1);
+        }
+        const uint32_t base = BUFS == 2 ? (uint32_t)(i & 1) * WL * 4 : 0u;
+        float* ob = outbuf + (BUFS == 2 ? (i & 1) * NF : 0);
+#pragma unroll
+        for (int p = 0; p < PAIRS; ++p) {
+            float acc_a = 0.f, acc_b = 0.f;
+            if (GATHER) {
+#pragma unroll
+                for (int q = 0; q < KTOT / 4; ++q)
+                    if (q * 4 < acap) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc_a = fmaf(wt[p][q * 4 + u], lds_gather16(pk[p], q * 4 + u, base), acc_a);
+                    }
+#pragma unroll
+                for (int q = 0; q < KTOT / 4; ++q)
+                    if (q * 4 >= KTOT - bcap) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc_b = fmaf(wt[p][q * 4 + u], lds_gather16(pk[p], q * 4 + u, base), acc_b);
+                    }
+            }
+            ob[(2 * p) * NT + threadIdx.x] = acc_a;
+            ob[(2 * p + 1) * NT + threadIdx.x] = acc_b;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("" : "+v"(token));
+        __syncthreads();
+        if (BUFS == 1 && COPY) leave(i);
+    }
+    if (BUFS == 2 && COPY) leave(b - 1);
+}
+
+__global__ void k_add_partials(const float4* __restrict__ partial, int n, size_t n4, float4* __restrict__ out) {
+    size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; v < n4; v += step) {
+        float4 a = partial[v];
+        for (int q = 1; q < n; ++q) {
+            const float4 t = partial[(size_t)q * n4 + v];
+            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        out[v] = a;
+    }
+}
+
 const char* const NAMES[] = {
     "hbm_read_GBps", "hbm_write_GBps", "hbm_copy_GBps_read_plus_write",
     "lds_gather_b32_random_lanes_per_clk_cu", "lds_gather_b32_conflict_free_lanes_per_clk_cu",
@@ -120,6 +248,9 @@ const char* const NAMES[] = {
     "l2_to_lds_row_copy_bytes_per_clk_cu", "l2_to_lds_row_copy_aggregate_GBps",
     "l2_piece_gather_3MiB_per_xcd_GBps", "l2_piece_gather_8MiB_per_xcd_GBps",
     "compute_units", "clock_GHz",
+    // the LDS form of the input gradient at m = 524288, d = 32768, k = 32, b = 256 (ms per call-equivalent)
+    "lds_form_one_buffer_distinct_banks_ms", "lds_form_one_buffer_random_banks_ms", "lds_form_add_16_partials_ms",
+    "lds_form_two_buffers_distinct_banks_ms", "lds_form_two_buffers_gathers_only_ms", "lds_form_two_buffers_copies_only_ms",
 };
 constexpr int NFIG = (int)(sizeof(NAMES) / sizeof(NAMES[0]));
 
@@ -227,6 +358,49 @@ extern "C" int usl_ceilings_run(double* values, int n) {
         CK(hipEventRecord(t.b, 0)); CK(hipEventSynchronize(t.b)); CK(hipEventElapsedTime(&ms, t.a, t.b));
         CK(hipGetLastError());
         out[11 + which] = (double)grid * 32.0 * trips * 8.0 * 128.0 / (ms * 1e-3) / 1e9;
+    }
+    {   // the LDS form of the input gradient: g = bufa (b x m floats), partial sums = bufb
+        const int b = 256, d = 32768;
+        const int64_t m = 16 * 32768;
+        auto time_form = [&](auto kern, int wl, int nf, int bufs, int acap, int bcap, int slot) -> hipError_t {
+            const size_t sh = ((size_t)wl * 4 + (size_t)nf * 4) * bufs;
+            const int nwin = (int)(m / wl), nfb = d / nf;
+            const int grid = ((nwin + 7) / 8) * 8 * nfb;
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), sh, 0, reinterpret_cast<const float*>(bufa), m, b, d, nfb, nwin,
+                               reinterpret_cast<float*>(bufb), acap, bcap);
+            if ((e = hipEventRecord(t.a, 0)) != hipSuccess) return e;
+            for (int r = 0; r < 3; ++r)
+                hipLaunchKernelGGL(kern, dim3(grid), dim3(1024), sh, 0, reinterpret_cast<const float*>(bufa), m, b, d, nfb, nwin,
+                                   reinterpret_cast<float*>(bufb), acap, bcap);
+            if ((e = hipEventRecord(t.b, 0)) != hipSuccess) return e;
+            if ((e = hipEventSynchronize(t.b)) != hipSuccess) return e;
+            float t_ms = 0.f;
+            if ((e = hipEventElapsedTime(&t_ms, t.a, t.b)) != hipSuccess) return e;
+            out[slot] = t_ms / 3;
+            return hipGetLastError();
+        };
+        CK(hipMemset(bufa, 0, (size_t)b * m * 4));
+        // one row buffer of 32768 labels, 2048 features per workgroup: lists of 36 + 32 of the 72 slots in use
+        CK(time_form(k_lds_form<72, 1, 32768, 1, 1, 1, 1>, 32768, 2048, 1, 36, 32, 15));
+        CK(time_form(k_lds_form<72, 1, 32768, 1, 0, 1, 1>, 32768, 2048, 1, 36, 32, 16));
+        {
+            const size_t n4 = (size_t)b * d / 4;
+            float4* sum = reinterpret_cast<float4*>(bufa);   // g is not needed while the partial sums are added
+            hipLaunchKernelGGL(k_add_partials, dim3(2048), dim3(256), 0, 0, reinterpret_cast<const float4*>(bufb), 16, n4, sum);
+            CK(hipEventRecord(t.a, 0));
+            for (int r = 0; r < 3; ++r)
+                hipLaunchKernelGGL(k_add_partials, dim3(2048), dim3(256), 0, 0, reinterpret_cast<const float4*>(bufb), 16, n4, sum);
+            CK(hipEventRecord(t.b, 0)); CK(hipEventSynchronize(t.b)); CK(hipEventElapsedTime(&ms, t.a, t.b));
+            CK(hipGetLastError());
+            out[17] = ms / 3;
+            CK(hipMemset(bufa, 0, (size_t)b * m * 4));
+        }
+        // two row buffers of 16384 labels, 4096 features per workgroup (two pairs per lane, 20 + 16 of 36 slots)
+        CK(time_form(k_lds_form<36, 2, 16384, 2, 1, 1, 1>, 16384, 4096, 2, 20, 16, 18));
+        CK(time_form(k_lds_form<36, 2, 16384, 2, 1, 0, 1>, 16384, 4096, 2, 20, 16, 19));
+        CK(time_form(k_lds_form<36, 2, 16384, 2, 1, 1, 0>, 16384, 4096, 2, 20, 16, 20));
     }
 done:
     (void)hipDeviceSynchronize();
