@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libusl.so")
 LIB_CEILINGS = os.path.join(HERE, "libusl_ceilings.so")   # measurement kernels, not part of the training path
 SOURCES = ["usl_api.hip", "k_products.hip", "k_elementwise.hip", "k_backward_input.hip",
-           "k_redistribute.hip", "k_schedule.hip", "k_predict.hip", "k_sparse_grad.hip"]
+           "k_redistribute.hip", "k_schedule.hip", "k_predict.hip", "k_sparse_grad.hip", "k_backward_input_lds.hip"]
 # -packed-fp32-ops: packed FP32 VALU instructions are switched off (they have produced wrong
 # results on the test machines); -munsafe-fp-atomics: hardware float atomic add, no CAS loop.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",

@@ -531,19 +531,25 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
     hipLaunchKernelGGL(k_zero_u32, dim3(c->num_cu), dim3(256), 0, c->stream, c->csc_cursor, nbins);
     hipLaunchKernelGGL(k_csc_fill, cgrid, dim3(CSC_NT), clds, c->stream, idx, c->m, c->k, c->d, wl,
                        splits, c->csc_ptr, rank_of, c->csc_cursor, c->csc_slot);
+    USL_TRY(usl_idx_fingerprint(c, idx, 1));
+    USL_TRY(usl_check_launch(c, "column lists"));
+    c->csc_built_for = idx;
+    c->lf_built_for = nullptr;   // one fingerprint: it belongs to the lists built last
+    return USL_OK;
+}
+
+}  // namespace
+
+usl_status usl_idx_fingerprint(usl_ctx* c, const int32_t* idx, int store) {
     if (!c->idx_print) {
         size_t cap = 0;
         USL_TRY(usl_reserve(c, (void**)&c->idx_print, &cap, 64));
         hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<uint32_t*>(c->idx_print), (size_t)16);
     }
-    hipLaunchKernelGGL(k_idx_fingerprint, dim3(1), dim3(1024), 0, c->stream, reinterpret_cast<const uint32_t*>(idx), N,
-                       c->idx_print, 1);
-    USL_TRY(usl_check_launch(c, "column lists"));
-    c->csc_built_for = idx;
+    hipLaunchKernelGGL(k_idx_fingerprint, dim3(1), dim3(1024), 0, c->stream, reinterpret_cast<const uint32_t*>(idx),
+                       (size_t)c->m * c->k, c->idx_print, store);
     return USL_OK;
 }
-
-}  // namespace
 
 // The batch goes through the gathers in groups of 256 instances (8 tiles, one per XCD): gT, its piece flags and
 // gxT are sized for one group, whatever the batch (at m = 3 million and b = 1024 that is 3 GB instead of 12).
@@ -632,7 +638,8 @@ usl_status usl_bwd_input_group(usl_ctx* c, float* grad_x_rows, int32_t rows, uin
 
 usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
                                      float* grad_x, int32_t b) {
-    USL_TRY(usl_bwd_input_prepare(c, idx, b));
+    const bool lds_form = usl_bwi_lds_applies(c);
+    if (!lds_form) USL_TRY(usl_bwd_input_prepare(c, idx, b));
     // a gradient that is almost all zeros goes through per-instance lists of its nonzeros instead; which of the
     // two paths does the work is decided on the device (gate), both are enqueued
     const uint32_t* gate = nullptr;
@@ -641,6 +648,7 @@ usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* 
         else USL_TRY(usl_sparse_compact(c, g, b, &gate));
         if (gate) USL_TRY(usl_sparse_backward_input(c, idx, W, grad_x, b));
     }
+    if (lds_form) return usl_bwi_lds_run(c, g, idx, W, grad_x, b, gate);
     USL_TRY(usl_bwd_input_gather_w(c, W, gate));
     const int G = usl_bwd_input_group_rows();
     for (int i0 = 0; i0 < b; i0 += G) {

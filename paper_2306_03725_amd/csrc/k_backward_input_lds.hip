@@ -1,0 +1,694 @@
+// Input gradient (Algorithm 2) in its feature-stationary LDS form: the mirror image of the forward kernel.
+//
+//   grad_x[i][c] = sum over connections (j,t) with idx[j][t]==c of W[j][t] * g[i][j]
+//
+// A workgroup owns a window of WL labels and a block of NF features.  Every lane keeps the list of one pair of
+// features -- (label-in-window, 16 bit) and weight of every connection that leads from the window into the feature
+// -- in registers for the workgroup's whole life, walks the batch staging g[i][window] (WL floats) through LDS with
+// LDS-DMA, and gathers: the same ds_read_b32 stream as the forward kernel, reading g row-major (no transposed copy
+// of the gradient, no zero flags).  The sums of a window go to partial[window][i][c]; a second kernel adds the
+// windows up.
+//
+// Lists of one (window, feature) have Poisson-distributed lengths (mean WL*k/d = 32 for the shapes this form is
+// used for), registers are allocated for a fixed number of slots.  Per (window, feature block) the features are
+// therefore ranked by list length and paired longest with shortest: lane l holds list A = rank l from slot 0 upwards
+// and list B = rank NF-1-l from slot KTOT-1 downwards; a wavefront (64 neighbouring ranks: nearly equal lengths)
+// visits slots [0, acap) for its A lists and [KTOT-bcap, KTOT) for its B lists, acap + bcap <= KTOT chosen per
+// wavefront so that as little as possible is left over.  Entries that do not fit (a few dozen per workgroup for
+// uniform connectivity: the very longest lists; anything for a caller's skewed idx) go to an overflow list of the
+// workgroup, kept list by list: its first 1024 entries sit in LDS with their weights and the list's own lane adds
+// them after its registers; what is beyond that is added with LDS atomics from memory: slow, rare, and what keeps
+// the form valid for any connectivity.  Within a lane's allowance the entries are put in a bank-aware order
+// (k_lf_schedule), the empty places of shorter lists included.
+//
+// Registers: 34 for the packed labels and 68 for the weights of the 68 slots leave 26 of a lane's 128 (1024 lanes
+// per compute unit) for everything else; the gathers are therefore written out in assembly, four in flight.
+#include <stdlib.h>
+
+#include "usl_internal.h"
+
+namespace {
+
+constexpr int WL = 32768;      // labels per window: one float32 row of 128 KiB in LDS
+constexpr int NF = 2048;       // features per workgroup (two per lane)
+constexpr int NT = 1024;
+constexpr int KTOT = 68;       // list slots per lane, shared by its two lists (with the rest of the kernel: the 128 registers a lane has)
+constexpr uint32_t PAD_SLOT = 0xFFFFFFFFu;
+constexpr int CHUNK = 32768;   // features per LDS histogram
+
+__global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// The slots of one window's labels, cut into `splits` contiguous shares.
+__device__ __forceinline__ void share_of(int64_t m, int k, int splits, size_t* e0, size_t* e1) {
+    const int w = blockIdx.x / splits, s = blockIdx.x % splits;
+    const size_t w0 = (size_t)w * WL * k;
+    const size_t w1 = (size_t)min((int64_t)(w + 1) * WL, m) * k;
+    const size_t per = (w1 - w0 + splits - 1) / splits;
+    *e0 = min(w0 + per * s, w1);
+    *e1 = min(*e0 + per, w1);
+}
+
+// count[w][c] += connections of this workgroup's share that lead into feature c (LDS histogram, then one global
+// atomic per feature that occurs).  grid (nwin * splits, feature chunks).
+__global__ void __launch_bounds__(NT)
+k_lf_count(const int32_t* __restrict__ idx, int64_t m, int k, int d, int splits, uint32_t* __restrict__ count) {
+    extern __shared__ uint32_t hist[];
+    const int c0 = blockIdx.y * CHUNK, nc = min(CHUNK, d - c0);
+    size_t e0, e1;
+    share_of(m, k, splits, &e0, &e1);
+    for (int q = threadIdx.x; q < nc; q += NT) hist[q] = 0;
+    __syncthreads();
+    for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
+        const uint32_t c = (uint32_t)(idx[e] - c0);
+        if (c < (uint32_t)nc) atomicAdd(&hist[c], 1u);
+    }
+    __syncthreads();
+    uint32_t* dst = count + (size_t)(blockIdx.x / splits) * d + c0;
+    for (int q = threadIdx.x; q < nc; q += NT)
+        if (hist[q]) atomicAdd(&dst[q], hist[q]);
+}
+
+// One workgroup per (window, feature block): ranks the block's NF features by list length, pairs them, fixes the
+// slot ranges of every wavefront and counts what will not fit.
+//   where[w][c]   = lane | zone << 10 | cap << 16   (zone 0 = list A, 1 = list B; cap = slots the list may use)
+//   feat[wg][z][lane] = feature (within the block) whose list lane holds in zone z
+//   caps[wg][wave]    = acap | bcap << 8
+//   ov_count[wg]      = entries beyond the caps; they are kept list by list:
+//   count[w][c]       becomes where the overflow of feature c starts in the workgroup's overflow list
+//   ovr[wg][z][lane]  = start | n << 16: the part of that list's overflow among the first NT entries (those the
+//                       gather kernel keeps in LDS and the list's own lane adds up)
+__global__ void __launch_bounds__(NT)
+k_lf_plan(uint32_t* __restrict__ count, int d, int nfb, uint32_t* __restrict__ where, uint16_t* __restrict__ feat,
+          uint32_t* __restrict__ caps, uint32_t* __restrict__ ov_count, uint32_t* __restrict__ ovr) {
+    __shared__ uint32_t start[256];
+    __shared__ uint32_t scan[NT];
+    __shared__ uint16_t len_of[2][NT];
+    __shared__ uint32_t cap_of[NT / 64];
+    const int wg = blockIdx.x, w = wg / nfb, fb = wg % nfb;
+    uint32_t* cnt = count + (size_t)w * d + (size_t)fb * NF;
+    if (threadIdx.x < 256) start[threadIdx.x] = 0;
+    __syncthreads();
+    uint32_t n[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        n[q] = cnt[threadIdx.x + q * NT];
+        atomicAdd(&start[min(n[q], 255u)], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {   // ranks of the buckets, longest lists first
+        uint32_t run = 0;
+        for (int q = 255; q >= 0; --q) { const uint32_t t = start[q]; start[q] = run; run += t; }
+    }
+    __syncthreads();
+    uint32_t lane_of[2], zone_of[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const uint32_t r = atomicAdd(&start[min(n[q], 255u)], 1u);   // rank (order among equal lengths is arbitrary)
+        zone_of[q] = r < (uint32_t)NT ? 0u : 1u;
+        lane_of[q] = r < (uint32_t)NT ? r : (uint32_t)(NF - 1) - r;
+        len_of[zone_of[q]][lane_of[q]] = (uint16_t)min(n[q], 65535u);
+        feat[((size_t)wg * 2 + zone_of[q]) * NT + lane_of[q]] = (uint16_t)(threadIdx.x + q * NT);
+    }
+    __syncthreads();
+    {   // the wavefront's two slot allowances (multiples of 4, KTOT together): those that leave the least outside
+        // the registers, counting the longest leftover of a single lane (its lane walks that alone) 16-fold
+        const uint32_t la = len_of[0][threadIdx.x], lb = len_of[1][threadIdx.x];
+        uint32_t best = 0xFFFFFFFFu;
+        for (uint32_t ca = 0; ca <= (uint32_t)KTOT; ca += 4) {
+            const uint32_t cb = (uint32_t)KTOT - ca;
+            uint32_t tot = (la > ca ? la - ca : 0u) + (lb > cb ? lb - cb : 0u);
+            uint32_t mx = max(la > ca ? la - ca : 0u, lb > cb ? lb - cb : 0u);
+            for (int o = 32; o > 0; o >>= 1) {
+                tot += __shfl_xor(tot, o);
+                mx = max(mx, (uint32_t)__shfl_xor(mx, o));
+            }
+            const uint32_t cost = min(tot + 16u * mx, 0xFFFFFFu);
+            best = min(best, cost << 8 | ca);
+        }
+        // no more than the longest list needs (slots a wavefront visits are time)
+        uint32_t amax = la, bmax = lb;
+        for (int o = 32; o > 0; o >>= 1) {
+            amax = max(amax, (uint32_t)__shfl_xor(amax, o));
+            bmax = max(bmax, (uint32_t)__shfl_xor(bmax, o));
+        }
+        const uint32_t acap = min(best & 0xFFu, (amax + 3u) & ~3u);
+        const uint32_t bcap = min((uint32_t)KTOT - (best & 0xFFu), (bmax + 3u) & ~3u);
+        if ((threadIdx.x & 63) == 0) {
+            cap_of[threadIdx.x >> 6] = acap | (bcap << 8);
+            caps[(size_t)wg * (NT / 64) + (threadIdx.x >> 6)] = acap | (bcap << 8);
+        }
+    }
+    __syncthreads();
+    uint32_t ov[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const uint32_t cw = cap_of[lane_of[q] >> 6];
+        const uint32_t cap = zone_of[q] == 0 ? (cw & 0xFFu) : (cw >> 8);
+        where[(size_t)w * d + (size_t)fb * NF + threadIdx.x + q * NT] = lane_of[q] | (zone_of[q] << 10) | (cap << 16);
+        ov[q] = n[q] > cap ? n[q] - cap : 0u;
+    }
+    scan[threadIdx.x] = ov[0] + ov[1];
+    __syncthreads();
+    for (int o = 1; o < NT; o <<= 1) {
+        const uint32_t t = threadIdx.x >= (unsigned)o ? scan[threadIdx.x - o] : 0u;
+        __syncthreads();
+        scan[threadIdx.x] += t;
+        __syncthreads();
+    }
+    uint32_t at = scan[threadIdx.x] - ov[0] - ov[1];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        cnt[threadIdx.x + q * NT] = at;
+        const uint32_t first = min(at, (uint32_t)NT);
+        ovr[((size_t)wg * 2 + zone_of[q]) * NT + lane_of[q]] = first | (min(ov[q], (uint32_t)NT - first) << 16);
+        at += ov[q];
+    }
+    if (threadIdx.x == NT - 1) ov_count[wg] = scan[NT - 1];
+}
+
+// ov_base[wg] = overflow entries of the workgroups before wg; ov_base[nwg] = all of them (one block).
+__global__ void __launch_bounds__(1024)
+k_lf_scan(const uint32_t* __restrict__ ov_count, int nwg, uint32_t* __restrict__ ov_base) {
+    __shared__ uint32_t part[1024];
+    const int per = (nwg + 1023) / 1024;
+    const int a = min(nwg, (int)threadIdx.x * per), e = min(nwg, a + per);
+    uint32_t s = 0;
+    for (int q = a; q < e; ++q) s += ov_count[q];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const uint32_t t = threadIdx.x >= (unsigned)o ? part[threadIdx.x - o] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += t;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - s;
+    for (int q = a; q < e; ++q) { ov_base[q] = run; run += ov_count[q]; }
+    if (threadIdx.x == 1023) ov_base[nwg] = part[1023];
+}
+
+// Places every connection: slot p of its list (p by a cursor: the order inside a list is not fixed) goes to register
+// slot p (list A) or KTOT-1-p (list B) of its lane, or to its list's part of the workgroup's overflow list.  Same decomposition as
+// k_lf_count: a share's positions in every list are reserved with one global atomic per feature, then handed out
+// from LDS cursors.
+struct OvEntry { uint16_t feature; uint16_t label; uint32_t slot; };
+__global__ void __launch_bounds__(NT)
+k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int nfb, int splits, const uint32_t* __restrict__ where,
+          uint32_t* __restrict__ taken, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot,
+          const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, OvEntry* __restrict__ ov) {
+    extern __shared__ uint32_t cur[];
+    const int c0 = blockIdx.y * CHUNK, nc = min(CHUNK, d - c0);
+    const int w = blockIdx.x / splits;
+    size_t e0, e1;
+    share_of(m, k, splits, &e0, &e1);
+    for (int q = threadIdx.x; q < nc; q += NT) cur[q] = 0;
+    __syncthreads();
+    for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
+        const uint32_t c = (uint32_t)(idx[e] - c0);
+        if (c < (uint32_t)nc) atomicAdd(&cur[c], 1u);
+    }
+    __syncthreads();
+    const size_t bin0 = (size_t)w * d + c0;
+    for (int q = threadIdx.x; q < nc; q += NT) {
+        const uint32_t n = cur[q];
+        if (n) cur[q] = atomicAdd(&taken[bin0 + q], n);
+    }
+    __syncthreads();
+    for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
+        const uint32_t c = (uint32_t)(idx[e] - c0);
+        if (c >= (uint32_t)nc) continue;
+        const uint32_t p = atomicAdd(&cur[c], 1u);
+        const uint32_t info = where[bin0 + c];
+        const uint32_t lane = info & 1023u, zone = (info >> 10) & 1u, cap = info >> 16;
+        const int col = c0 + (int)c;
+        const size_t wg = (size_t)w * nfb + col / NF;
+        const uint16_t lab16 = (uint16_t)((int64_t)(e / (size_t)k) - (int64_t)w * WL);
+        if (p < cap) {
+            const uint32_t t = zone == 0 ? p : (uint32_t)(KTOT - 1) - p;
+            const size_t at = (wg * KTOT + t) * NT + lane;
+            lab[at] = lab16;
+            slot[at] = (uint32_t)e;
+        } else {
+            OvEntry o;
+            o.feature = (uint16_t)(col % NF); o.label = lab16; o.slot = (uint32_t)e;
+            ov[(size_t)ov_base[wg] + ov_off[bin0 + c] + (p - cap)] = o;
+        }
+    }
+}
+
+// Bank-aware order of the entries in every lane's lists.  At step t of the gathers the 32 lanes of a half-wavefront
+// read slot t of their own lists; the sum does not depend on the order of a list, so each list is permuted so that
+// the 32 addresses of a step fall into different LDS banks as far as possible (a step costs as many LDS cycles as its
+// fullest bank has lanes).  The order is built step by step as a sequence of matchings between the 32 lanes and the
+// 32 banks over the entries not placed yet -- a few rounds of proposals, then augmenting paths from the banks still
+// free, then lanes whose banks are all taken double up on the least loaded one --, the same construction as for the
+// slots of a label in the forward product, with one addition: a list shorter than the wavefront's allowance has
+// empty places, which may go to any step and read any bank.  A lane that finds no bank among its entries spends an
+// empty place (reading a label whose bank is free: with a zero weight) while it has one.
+// One half-wavefront per (workgroup of the gather kernel, zone, 32 lanes); lane i is list i and also bank i.
+// Reads the lists as filled (lab0 / slot0), writes them ordered (lab / slot).  Any outcome is a valid order: it
+// changes speed, never results.
+constexpr int SG = 8;   // half-wavefronts per workgroup
+__global__ void __launch_bounds__(SG * 32)
+k_lf_schedule(const uint16_t* __restrict__ lab0, const uint32_t* __restrict__ slot0, const uint32_t* __restrict__ caps,
+              int64_t m, int nfb, int rounds, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot) {
+    __shared__ uint8_t slots[SG][32][KTOT + 4];   // first the bank of every entry, then my entries sorted by bank
+    __shared__ uint8_t ord[SG][32][KTOT + 4];     // entry read at step s (0x80 | bank: an empty place)
+    __shared__ uint8_t left_in[SG][32][36];       // entries of mine not placed yet, per bank
+    __shared__ uint8_t end_of[SG][32][36];        // where bank b's entries end in the sorted list
+    __shared__ int deg0[SG][32];
+    __shared__ int win[SG][32];
+    const int gl = threadIdx.x >> 5, lane = threadIdx.x & 31;
+    const int hs = threadIdx.x & 32;              // where my group's 32 bits sit in a wavefront ballot
+    const size_t gid = (size_t)blockIdx.x * SG + gl;
+    const size_t wg = gid >> 6;
+    const int zone = (int)(gid >> 5) & 1, half = (int)gid & 31;   // the two halves of a wavefront are neighbours: same allowance
+    const uint32_t cw = caps[wg * (NT / 64) + (half >> 1)];
+    const int cap = zone ? (int)(cw >> 8) : (int)(cw & 0xFFu);
+    const int w = (int)(wg / nfb);
+    const bool wide = m - (int64_t)w * WL >= 32;   // the window has a label for every bank
+    auto at = [&](int p) -> size_t { return (wg * KTOT + (zone ? KTOT - 1 - p : p)) * NT + half * 32 + lane; };
+    deg0[gl][lane] = 0;
+    for (int b = 0; b < 32; ++b) left_in[gl][lane][b] = 0;
+    __syncthreads();
+    uint8_t* mine = slots[gl][lane];
+    uint8_t* cnt = left_in[gl][lane];
+    uint8_t* ends = end_of[gl][lane];
+    int n = 0;                     // entries of my list (they sit in its first places)
+    for (int p = 0; p < cap; ++p) {
+        if (slot0[at(p)] == PAD_SLOT) break;
+        const int b = lab0[at(p)] & 31;
+        mine[p] = (uint8_t)b;
+        ++cnt[b];
+        atomicAdd(&deg0[gl][b], 1);
+        n = p + 1;
+    }
+    int wild = cap - n;            // empty places left
+    uint32_t avail = 0;            // banks my unplaced entries read
+    {   // counting sort of my entries by bank, in place through ord (free until the first step)
+        int run = 0;
+        for (int b = 0; b < 32; ++b) { run += cnt[b]; ends[b] = (uint8_t)run; if (cnt[b]) avail |= 1u << b; }
+        uint8_t* tmp = ord[gl][lane];
+        for (int p = 0; p < n; ++p) tmp[p] = mine[p];
+        for (int p = n - 1; p >= 0; --p) { const int b = tmp[p]; ends[b] = (uint8_t)(ends[b] - 1); mine[ends[b]] = (uint8_t)p; }
+        for (int b = 0; b < 32; ++b) ends[b] = (uint8_t)(ends[b] + cnt[b]);   // back from starts to ends
+    }
+    __syncthreads();
+    auto gballot = [&](bool p) -> uint32_t { return (uint32_t)(__ballot(p) >> hs); };
+    volatile int* gwin = win[gl];
+    int mydeg = deg0[gl][lane];    // bank role: entries of the group that read bank `lane` and are not placed yet
+    for (int s = 0; s < cap; ++s) {
+        int mb = -1;               // list role: my bank at this step
+        int ml = -1;               // bank role: the list that reads me at this step
+        for (int r = 0; r < rounds; ++r) {
+            const uint32_t freeb = gballot(ml < 0);
+            gwin[lane] = 255;
+            int prop = -1;
+            const uint32_t cand = mb < 0 ? (avail & freeb) : 0u;
+            if (cand) {            // first candidate bank at or after a lane- and round-dependent start
+                const int sh = (lane + 7 * r) & 31;
+                const uint32_t rc = (cand >> sh) | (cand << ((32 - sh) & 31));
+                prop = (__ffs(rc) - 1 + sh) & 31;
+                atomicMin(&win[gl][prop], lane);
+            }
+            const int wnr = gwin[lane];
+            if (ml < 0 && wnr < 32) ml = wnr;
+            if (prop >= 0 && gwin[prop] == lane) mb = prop;
+        }
+        // augmenting paths from the banks still free
+        uint32_t todo = gballot(ml < 0 && mydeg > 0);
+        while (__any(todo != 0)) {
+            const bool act = todo != 0;
+            const int b0 = act ? __ffs(todo) - 1 : 0;
+            todo &= todo - 1;
+            uint32_t front = act ? (1u << b0) : 0u, seen = 0;
+            int par = -1, found = -1;
+            bool searching = act;
+            while (__any(searching)) {
+                const bool reach = searching && !((seen >> lane) & 1u) && (avail & front) != 0;
+                if (reach) par = __ffs(avail & front) - 1;
+                const uint32_t fresh = gballot(reach);
+                const uint32_t fresh_free = gballot(reach && mb < 0);
+                const uint32_t next = gballot(ml >= 0 && ((fresh >> (ml & 31)) & 1u));
+                seen |= fresh;
+                if (searching) {
+                    if (fresh_free) { found = __ffs(fresh_free) - 1; searching = false; }
+                    else if (next == 0) searching = false;
+                    else front = next;
+                }
+            }
+            int cur = found;       // walk back: every list on the path takes the bank it was reached through
+            while (__any(cur >= 0)) {
+                const bool a = cur >= 0;
+                const int cl = a ? cur : 0;
+                const int b = __shfl(par, cl, 32) & 31;
+                const int prev = __shfl(ml, b, 32);
+                if (a) {
+                    if (lane == cl) mb = b;
+                    if (lane == b) ml = cl;
+                    cur = b == b0 ? -1 : prev;
+                }
+            }
+        }
+        // lists without a bank: an empty place if one is left, on a bank nobody reads (there are as many free banks as
+        // lists without one)
+        int wb = -1;
+        {
+            const bool spend = mb < 0 && wild > 0;
+            const uint32_t spenders = gballot(spend);
+            uint32_t fb = gballot(ml < 0);
+            if (spend) {
+                for (int q = __popc(spenders & ((1u << lane) - 1u)); q > 0; --q) fb &= fb - 1;
+                wb = __ffs(fb) - 1;
+                --wild;
+            }
+        }
+        // the others double up: least loaded reachable bank, then the fullest
+        int myload = ml >= 0 ? 1 : 0;
+        uint32_t left = gballot(mb < 0 && wb < 0);
+        while (__any(left != 0)) {
+            const bool a = left != 0;
+            const int l = a ? __ffs(left) - 1 : 0;
+            left &= left - 1;
+            const uint32_t av = (uint32_t)__shfl((int)avail, l, 32);
+            int key = (a && ((av >> lane) & 1u)) ? (((255 - myload) << 17) | (mydeg << 5) | lane) : -1;
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) key = max(key, __shfl_xor(key, o, 32));
+            if (a && key >= 0) {
+                const int bb = key & 31;
+                if (lane == l) mb = bb;
+                if (lane == bb) ++myload;
+            }
+        }
+        if (wb >= 0) {
+            ord[gl][lane][s] = (uint8_t)(0x80 | wb);
+        } else {                   // my next unplaced entry in that bank
+            const int pick = mine[ends[mb] - cnt[mb]];
+            if (--cnt[mb] == 0) avail &= ~(1u << mb);
+            ord[gl][lane][s] = (uint8_t)pick;
+        }
+        mydeg -= myload;
+    }
+    for (int s = 0; s < cap; ++s) {
+        const int o = ord[gl][lane][s];
+        const bool empty = (o & 0x80) != 0;
+        lab[at(s)] = empty ? (uint16_t)(wide ? (o & 31) : 0) : lab0[at(o)];
+        slot[at(s)] = empty ? PAD_SLOT : slot0[at(o)];
+    }
+}
+
+typedef const __attribute__((address_space(3))) float lds_f32_t;
+// acc += sum of w[u] * row[label u] over the four labels packed in p0, p1 (16 bits each).  One instruction per
+// address (the 16-bit half is selected and scaled to a byte offset in one go; the row starts at LDS address 0: the
+// kernel has no static LDS, and the launcher checks that), the four reads in flight together, each multiply-add as
+// soon as its value is there.  Written out because the compiler, short of registers in this kernel, issues one read
+// at a time and waits for it.
+__device__ __forceinline__ void gather4(float& acc, uint32_t p0, uint32_t p1, float w0, float w1, float w2, float w3) {
+    uint32_t a0, a1, a2, a3;
+    const uint32_t two = 2;
+    asm volatile(
+        "v_lshlrev_b32_sdwa %1, %5, %6 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "v_lshlrev_b32_sdwa %2, %5, %6 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "v_lshlrev_b32_sdwa %3, %5, %7 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n\t"
+        "v_lshlrev_b32_sdwa %4, %5, %7 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n\t"
+        "ds_read_b32 %1, %1\n\t"
+        "ds_read_b32 %2, %2\n\t"
+        "ds_read_b32 %3, %3\n\t"
+        "ds_read_b32 %4, %4\n\t"
+        "s_waitcnt lgkmcnt(3)\n\t"
+        "v_fmac_f32 %0, %8, %1\n\t"
+        "s_waitcnt lgkmcnt(2)\n\t"
+        "v_fmac_f32 %0, %9, %2\n\t"
+        "s_waitcnt lgkmcnt(1)\n\t"
+        "v_fmac_f32 %0, %10, %3\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fmac_f32 %0, %11, %4"
+        : "+v"(acc), "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3)
+        : "s"(two), "v"(p0), "v"(p1), "v"(w0), "v"(w1), "v"(w2), "v"(w3)
+        : "memory");
+}
+
+// The gathers.  grid: ceil(nwin / 8) * 8 * nfb workgroups; all feature blocks of a window run on one XCD (workgroups
+// are dealt to the 8 XCDs round robin), so its slice of g is fetched from HBM once and served from that XCD's L2.
+// LDS: [0, WL*4) the row slice, then NF floats through which the sums are un-permuted, then NT words: the features
+// of every lane, then NT entries of 8 bytes: the nearest part of the overflow list, then
+// 2 * NT words: each lane's share of it.
+template <typename TS>
+__global__ void __launch_bounds__(NT)
+k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int k, int rows, int d, int nfb, int nwin,
+          const uint16_t* __restrict__ lab, const uint32_t* __restrict__ slot, const uint16_t* __restrict__ feat,
+          const uint32_t* __restrict__ caps, const uint32_t* __restrict__ ov_base, const OvEntry* __restrict__ ov,
+          const uint32_t* __restrict__ ovr, float* __restrict__ partial, const uint32_t* __restrict__ gate) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    if (gate && *gate == 0) return;   // the kernels over the nonzero gradients do this call's work
+    const int w = (blockIdx.x & 7) + 8 * (blockIdx.x / (8 * nfb)), fb = (blockIdx.x >> 3) % nfb;
+    if (w >= nwin) return;
+    const size_t wg = (size_t)w * nfb + fb;
+    const uint32_t cw = caps[wg * (NT / 64) + (threadIdx.x >> 6)];
+    const int acap = __builtin_amdgcn_readfirstlane((int)(cw & 0xFFu)), bcap = __builtin_amdgcn_readfirstlane((int)(cw >> 8));
+    uint32_t pk[KTOT / 2];
+    float wt[KTOT];
+    const uint32_t last_slot = (uint32_t)(m * k - 1);
+#pragma unroll
+    for (int q = 0; q < KTOT / 4; ++q) {
+        const bool used = q * 4 < acap || q * 4 >= KTOT - bcap;   // the same for the whole wavefront
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = q * 4 + u;
+            uint32_t l16 = 0;
+            float wv = 0.f;
+            if (used) {
+                const size_t at = (wg * KTOT + t) * NT + threadIdx.x;
+                l16 = lab[at];
+                const uint32_t s = slot[at];
+                wv = usl_load_f32<TS>(W, (size_t)min(s, last_slot));   // an empty place reads some weight and drops it
+                wv = s != PAD_SLOT ? wv : 0.f;
+            }
+            if (t & 1) pk[t >> 1] |= l16 << 16; else pk[t >> 1] = l16;
+            wt[t] = wv;
+        }
+    }
+    const uint32_t ov0 = ov_base[wg], ov_n = ov_base[wg + 1] - ov0;
+    float* row = reinterpret_cast<float*>(lds_raw);
+    float* outbuf = row + WL;
+    // which features the lane's two sums belong to: kept in LDS, not in registers (the lists need those)
+    uint32_t* feat_of = reinterpret_cast<uint32_t*>(outbuf + NF);
+    feat_of[threadIdx.x] = (uint32_t)feat[(wg * 2 + 0) * NT + threadIdx.x] | (uint32_t)feat[(wg * 2 + 1) * NT + threadIdx.x] << 16;
+    // the first NT entries that did not fit the registers, with their weights: {feature | label << 16, weight}
+    uint2* ov_near = reinterpret_cast<uint2*>(feat_of + NT);
+    if (threadIdx.x < ov_n) {
+        const OvEntry o = ov[(size_t)ov0 + threadIdx.x];
+        ov_near[threadIdx.x] = make_uint2((uint32_t)o.label * 4u, __float_as_uint(usl_load_f32<TS>(W, (size_t)o.slot)));
+    } else {
+        ov_near[threadIdx.x] = make_uint2(0u, 0u);
+    }
+    // ... and which of them belong to the lane's two lists (start | n << 16)
+    uint32_t* ovr_a = reinterpret_cast<uint32_t*>(ov_near + NT);
+    uint32_t* ovr_b = ovr_a + NT;
+    ovr_a[threadIdx.x] = ovr[(wg * 2 + 0) * NT + threadIdx.x];
+    ovr_b[threadIdx.x] = ovr[(wg * 2 + 1) * NT + threadIdx.x];
+    const int nl = (int)min((int64_t)WL, m - (int64_t)w * WL);   // labels of this window (the last one may be short)
+    const int nv = nl / 4, full = nv & ~63;                      // 16-byte pieces of a row slice; those in whole 1 KiB runs
+    const int lines = (nl * 4 + 127) / 128, per = (lines + nfb - 1) / nfb;   // 128-byte lines; this workgroup's share of the warm-up
+    const bool warms = (int)threadIdx.x < per && fb * per + (int)threadIdx.x < lines;
+    // the rest of a list (r = start | n << 16 in ov_near), two entries in flight at a time
+    auto more = [&](float& acc, uint32_t r) {
+        for (uint32_t q = r & 0xFFFFu, n = r >> 16; n; q += 2, n = n > 2 ? n - 2 : 0) {
+            const uint2 o0 = ov_near[q], o1 = ov_near[min(q + 1, (uint32_t)NT - 1)];
+            const float v0 = *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(o0.x));
+            const float v1 = *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(o1.x));
+            acc = fmaf(__uint_as_float(o0.y), v0, acc);
+            acc = fmaf(n > 1 ? __uint_as_float(o1.y) : 0.f, v1, acc);
+        }
+    };
+    uint32_t token = 0;   // receives the L2 warm-up loads; reserved until the next vmcnt(0) wait
+    for (int i = 0; i < rows; ++i) {
+        const char* grow = reinterpret_cast<const char*>(g + (size_t)w * WL + (size_t)i * m);   // uniform
+        {   // the row slice: whole 1 KiB pieces by LDS-DMA, the ragged end through registers
+            for (int v = (threadIdx.x >> 6) * 64; v < full; v += NT)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + ((uint32_t)v * 16u + (threadIdx.x & 63u) * 16u)),
+                                                 (__attribute__((address_space(3))) void*)(lds_raw + (size_t)v * 16), 16, 0, 0);
+            for (int v = full + threadIdx.x; v < nv; v += NT)
+                reinterpret_cast<uint4*>(lds_raw)[v] = reinterpret_cast<const uint4*>(grow)[v];
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("" : "+v"(token));
+        }
+        __syncthreads();
+        if (i + 1 < rows && warms)   // the window's workgroups share the warm-up of the next row slice, one load per 128-byte line
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(token) : "v"((uint32_t)(fb * per + (int)threadIdx.x) * 128u), "s"(grow + (size_t)m * 4));
+        float acc_a = 0.f, acc_b = 0.f;
+#pragma unroll
+        for (int q = 0; q < KTOT / 4; ++q) {
+            if (q * 4 < acap) {
+                gather4(acc_a, pk[q * 2], pk[q * 2 + 1], wt[q * 4], wt[q * 4 + 1], wt[q * 4 + 2], wt[q * 4 + 3]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < KTOT / 4; ++q) {
+            if (q * 4 >= KTOT - bcap) {
+                gather4(acc_b, pk[q * 2], pk[q * 2 + 1], wt[q * 4], wt[q * 4 + 1], wt[q * 4 + 2], wt[q * 4 + 3]);
+            }
+        }
+        if (ov_n) {   // the same for the whole workgroup: the few lanes whose lists did not fit go on through LDS
+            more(acc_a, ovr_a[threadIdx.x]);
+            more(acc_b, ovr_b[threadIdx.x]);
+        }
+        {
+            const uint32_t f = feat_of[threadIdx.x];
+            outbuf[f & 0xFFFFu] = acc_a;
+            outbuf[f >> 16] = acc_b;
+        }
+        if (ov_n > (uint32_t)NT) {   // only a skewed connectivity gets here: what LDS does not hold, by atomics
+            __syncthreads();
+            for (uint32_t q = NT + threadIdx.x; q < ov_n; q += NT) {
+                const OvEntry o = ov[(size_t)ov0 + q];
+                unsafeAtomicAdd(&outbuf[o.feature], usl_load_f32<TS>(W, (size_t)o.slot) * row[o.label]);
+            }
+        }
+        __syncthreads();
+        {   // the block's NF sums leave as one contiguous run
+            float* dst = partial + ((size_t)w * rows + i) * d + (size_t)fb * NF;
+            for (int v = threadIdx.x; v < NF / 4; v += NT)
+                reinterpret_cast<float4*>(dst)[v] = reinterpret_cast<const float4*>(outbuf)[v];
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("" : "+v"(token));
+}
+
+// grad_x[i][c] = sum over the windows of partial[w][i][c]
+__global__ void __launch_bounds__(256)
+k_lf_reduce(const float4* __restrict__ partial, int nwin, size_t n4, float4* __restrict__ out,
+            const uint32_t* __restrict__ gate, const uint32_t* __restrict__ stale) {
+    if (gate && *gate == 0) return;
+    const bool poison = *stale != 0;   // the lists were built from other contents of idx: no number is better than a wrong one
+    size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; v < n4; v += step) {
+        float4 a = partial[v];
+        for (int q = 1; q < nwin; ++q) {
+            const float4 t = partial[(size_t)q * n4 + v];
+            a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+        }
+        if (poison) a.x = a.y = a.z = a.w = __uint_as_float(0x7FC00000u);
+        out[v] = a;
+    }
+}
+
+}  // namespace
+
+// Is this layer one for the LDS form?  Lists of about 32 entries per (window, feature) -- WL*k == 32*d --, whole
+// feature blocks, 16-byte aligned rows of g, and enough (window, feature block) workgroups to fill the chip.
+// USL_TUNE_BWI=lds forces it where the shape allows at all, =l2 forbids it.
+bool usl_bwi_lds_applies(const usl_ctx* c) {
+    const bool shape_ok = c->d % NF == 0 && c->d <= 65536 && c->m % 4 == 0 && (int64_t)WL * c->k == (int64_t)32 * c->d &&
+                          c->m * (int64_t)c->k < (int64_t)PAD_SLOT;
+    if (!shape_ok) return false;
+    if (const char* e = getenv("USL_TUNE_BWI")) {
+        if (!strcmp(e, "lds")) return true;
+        if (!strcmp(e, "l2")) return false;
+    }
+    const int64_t nwin = (c->m + WL - 1) / WL;
+    return nwin * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
+}
+
+static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
+    const size_t N = (size_t)c->m * c->k;
+    const int nwin = (int)((c->m + WL - 1) / WL), nfb = c->d / NF, nwg = nwin * nfb;
+    const size_t nbins = (size_t)nwin * c->d;
+    USL_TRY(usl_reserve(c, (void**)&c->lf_count, &c->lf_count_cap, nbins * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_taken, &c->lf_taken_cap, nbins * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_where, &c->lf_where_cap, nbins * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_feat, &c->lf_feat_cap, (size_t)nwg * 2 * NT * 2));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_caps, &c->lf_caps_cap, (size_t)nwg * (NT / 64) * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ov_base, &c->lf_ov_base_cap, ((size_t)nwg * 2 + 1) * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ovr, &c->lf_ovr_cap, (size_t)nwg * 2 * NT * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_lab, &c->lf_lab_cap, (size_t)nwg * KTOT * NT * 2));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_slot, &c->lf_slot_cap, (size_t)nwg * KTOT * NT * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ov, &c->lf_ov_cap, N * sizeof(OvEntry)));
+    int rounds = 3;                // of proposals per step of the bank-aware order; 0 = lists stay as filled
+    if (const char* e = getenv("USL_TUNE_ROUNDS")) rounds = atoi(e);
+    uint16_t* lab0 = c->lf_lab;
+    uint32_t* slot0 = c->lf_slot;
+    if (rounds > 0) {
+        USL_TRY(usl_reserve(c, (void**)&c->lf_lab0, &c->lf_lab0_cap, (size_t)nwg * KTOT * NT * 2));
+        USL_TRY(usl_reserve(c, (void**)&c->lf_slot0, &c->lf_slot0_cap, (size_t)nwg * KTOT * NT * 4));
+        lab0 = c->lf_lab0;
+        slot0 = c->lf_slot0;
+    }
+    uint32_t* ov_base = c->lf_ov_base;
+    uint32_t* ov_count = c->lf_ov_base + nwg + 1;
+    const unsigned chunks = (unsigned)((c->d + CHUNK - 1) / CHUNK);
+    int splits = (int)((size_t)c->num_cu / ((size_t)nwin * chunks));
+    splits = splits < 1 ? 1 : splits > 16 ? 16 : splits;
+    const dim3 grid((unsigned)(nwin * splits), chunks);
+    const size_t lds = (size_t)(c->d < CHUNK ? c->d : CHUNK) * 4;
+    USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(k_lf_count), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(k_lf_fill), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const dim3 fillg(c->num_cu * 4), fillb(256);
+    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_count, nbins, 0u);
+    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_taken, nbins, 0u);
+    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, slot0, (size_t)nwg * KTOT * NT, PAD_SLOT);
+    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, reinterpret_cast<uint32_t*>(lab0), (size_t)nwg * KTOT * NT / 2, 0u);
+    hipLaunchKernelGGL(k_lf_count, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, splits, c->lf_count);
+    hipLaunchKernelGGL(k_lf_plan, dim3((unsigned)nwg), dim3(NT), 0, c->stream, c->lf_count, c->d, nfb, c->lf_where, c->lf_feat,
+                       c->lf_caps, ov_count, c->lf_ovr);
+    hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, ov_count, nwg, ov_base);
+    hipLaunchKernelGGL(k_lf_fill, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, nfb, splits, c->lf_where, c->lf_taken,
+                       lab0, slot0, ov_base, c->lf_count, reinterpret_cast<OvEntry*>(c->lf_ov));
+    if (rounds > 0)
+        hipLaunchKernelGGL(k_lf_schedule, dim3((unsigned)(nwg * 64 / SG)), dim3(SG * 32), 0, c->stream, lab0, slot0, c->lf_caps,
+                           c->m, nfb, rounds, c->lf_lab, c->lf_slot);
+    USL_TRY(usl_idx_fingerprint(c, idx, 1));
+    USL_TRY(usl_check_launch(c, "register lists of the input gradient"));
+    c->lf_built_for = idx;
+    c->csc_built_for = nullptr;   // one fingerprint: it belongs to the lists built last
+    return USL_OK;
+}
+
+// grad_x[b][d] from g[b][m] (row-major).  gate as for the other dense kernels.
+usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const void* W, float* grad_x, int32_t b,
+                           const uint32_t* gate) {
+    // same address as when the lists were built: check that the contents are the same (else grad_x becomes NaN and
+    // usl_check reports it)
+    if (c->lf_built_for != idx) USL_TRY(lf_build(c, idx));
+    else USL_TRY(usl_idx_fingerprint(c, idx, 0));
+    const uint32_t* stale = reinterpret_cast<const uint32_t*>(c->idx_print) + 4;
+    const int nwin = (int)((c->m + WL - 1) / WL), nfb = c->d / NF, nwg = nwin * nfb;
+    const int G = 256;   // instances per pass: the partial sums of one pass are nwin * G * d floats
+    const int rows_max = c->max_b < G ? c->max_b : G;
+    USL_TRY(usl_reserve(c, (void**)&c->lf_partial, &c->lf_partial_cap, (size_t)nwin * rows_max * c->d * 4));
+    const size_t lds = (size_t)WL * 4 + (size_t)NF * 4 + (size_t)NT * 4 + (size_t)NT * 8 + (size_t)NT * 8;
+    const unsigned grid = (unsigned)(((nwin + 7) / 8) * 8 * nfb);
+    const uint32_t* ov_base = c->lf_ov_base;
+    (void)nwg;
+    static bool checked[2] = {false, false};
+    for (int i0 = 0; i0 < b; i0 += G) {
+        const int rows = b - i0 < G ? b - i0 : G;
+#define USL_LDS_FORM(TS, WHICH)                                                                                          \
+        do {                                                                                                             \
+            if (!checked[WHICH]) {                                                                                       \
+                hipFuncAttributes fa;                                                                                    \
+                USL_HIP(c, hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(k_bwi_lds<TS>)));                     \
+                if (fa.sharedSizeBytes != 0)                                                                             \
+                    USL_FAIL(c, USL_EUNSUPPORTED, "backward_input (LDS form): the kernel has static LDS, its row buffer " \
+                                                  "does not start at LDS address 0");                                    \
+                USL_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(k_bwi_lds<TS>),                             \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
+                checked[WHICH] = true;                                                                                   \
+            }                                                                                                            \
+            hipLaunchKernelGGL(k_bwi_lds<TS>, dim3(grid), dim3(NT), lds, c->stream, g + (size_t)i0 * c->m, (const TS*)W, \
+                               c->m, c->k, rows, c->d, nfb, nwin, c->lf_lab, c->lf_slot, c->lf_feat, c->lf_caps, ov_base,      \
+                               reinterpret_cast<const OvEntry*>(c->lf_ov), c->lf_ovr, c->lf_partial, gate);                         \
+        } while (0)
+        if (c->storage == USL_F32) USL_LDS_FORM(float, 0); else USL_LDS_FORM(uint16_t, 1);
+#undef USL_LDS_FORM
+        const size_t n4 = (size_t)rows * c->d / 4;
+        hipLaunchKernelGGL(k_lf_reduce, dim3(c->num_cu * 8), dim3(256), 0, c->stream,
+                           reinterpret_cast<const float4*>(c->lf_partial), nwin, n4,
+                           reinterpret_cast<float4*>(grad_x + (size_t)i0 * c->d), gate, stale);
+    }
+    return usl_check_launch(c, "backward_input (LDS form)");
+}

@@ -59,6 +59,22 @@ struct usl_ctx {
     uint32_t* hint_dev;       // the same words as the device addresses them
     uint32_t hint_seen, probe_serial;
     int sparse_streak;        // looks in a row that found the sample sparse
+    // the input gradient's feature-stationary form (k_backward_input_lds.hip): per (label window, feature block)
+    // workgroup the register lists of its lanes, their plan, what did not fit, and the windows' partial sums
+    uint32_t* lf_count;       size_t lf_count_cap;    // [nwin*d] list lengths, then where a list's overflow starts
+    uint32_t* lf_taken;       size_t lf_taken_cap;    // [nwin*d] positions handed out while filling
+    uint32_t* lf_where;       size_t lf_where_cap;    // [nwin*d] lane, zone and slot allowance of a feature's list
+    uint16_t* lf_feat;        size_t lf_feat_cap;     // [wg][2][1024] feature of a lane's list
+    uint32_t* lf_caps;        size_t lf_caps_cap;     // [wg][16] slots the wavefronts visit
+    uint32_t* lf_ov_base;     size_t lf_ov_base_cap;  // [wg+1] start of a workgroup's overflow entries, then [wg] their number
+    uint32_t* lf_ovr;         size_t lf_ovr_cap;      // [wg][2][1024] a lane's lists' share of the overflow entries held in LDS
+    uint16_t* lf_lab;         size_t lf_lab_cap;      // [wg][slots][1024] label within the window
+    uint32_t* lf_slot;        size_t lf_slot_cap;     // [wg][slots][1024] flat slot j*k+t (where the weight lives)
+    uint16_t* lf_lab0;        size_t lf_lab0_cap;     // the same two as filled, before the bank-aware order
+    uint32_t* lf_slot0;       size_t lf_slot0_cap;
+    void* lf_ov;              size_t lf_ov_cap;       // overflow entries
+    float* lf_partial;        size_t lf_partial_cap;  // [nwin][rows of a pass][d]
+    const int32_t* lf_built_for;                      // idx pointer the lists were built from (NULL = stale)
 };
 
 #define USL_FAIL(ctx, code, ...)                                   \
@@ -112,6 +128,14 @@ usl_status usl_bwd_input_gather_w(usl_ctx* ctx, const void* W, const uint32_t* g
 usl_status usl_bwd_input_begin_group(usl_ctx* ctx);
 usl_status usl_bwd_input_group(usl_ctx* ctx, float* grad_x_rows, int32_t rows, uint64_t sampled_labels,
                                const uint32_t* gate);
+// The same product with the lists of each (label window, 2048 features) held in registers and the rows of g staged
+// through LDS (k_backward_input_lds.hip); applies to shapes with about 32 connections per (window, feature).
+bool usl_bwi_lds_applies(const usl_ctx* ctx);
+usl_status usl_bwi_lds_run(usl_ctx* ctx, const float* g, const int32_t* idx, const void* W, float* grad_x, int32_t b,
+                           const uint32_t* gate);
+// Records (store = 1) the fingerprint of idx in ctx->idx_print, or compares with the recorded one (store = 0) and
+// raises the stale word (32-bit word 4 of idx_print) on a difference.
+usl_status usl_idx_fingerprint(usl_ctx* ctx, const int32_t* idx, int store);
 static inline uint32_t* usl_nz_cells(usl_ctx* c) { return reinterpret_cast<uint32_t*>(c->counter64) + 4; }
 // Loss and gradient in place on zg[b][m], which also leaves the gradient in c->gT (tile-major) with
 // its piece flags and sampled nonzero count (usl_bwd_input_prepare must have run); *sampled_labels

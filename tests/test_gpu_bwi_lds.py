@@ -1,0 +1,139 @@
+"""The input gradient (Algorithm 2) in its register-list form -- lists of each (window of 32768 labels, 2048
+features) in registers, rows of g staged through LDS -- against the oracle, element by element (1e-4, as for the
+other form).  The form applies where 32768 * k == 32 * d; USL_TUNE_BWI=lds switches it on below the size at which
+the library would choose it by itself."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+
+# (m, d, k, b, storage)
+SHAPES = [
+    (70000, 2048, 2, 5, "f32"),       # three windows, the last one short with a ragged end of 16-byte pieces
+    (32772, 2048, 2, 3, "f32"),       # a second window of four labels
+    (100000, 8192, 8, 37, "f32"),     # four feature blocks
+    (40000, 32768, 32, 3, "f32"),     # the headline's d and k
+    (40000, 32768, 32, 3, "bf16"),
+    (66000, 65536, 64, 2, "bf16"),    # d of two histogram chunks
+    (70000, 2048, 2, 300, "f32"),     # two passes over the batch (256 + 44 instances)
+]
+
+
+@pytest.fixture()
+def lds_form(monkeypatch):
+    monkeypatch.setenv("USL_TUNE_BWI", "lds")
+
+
+@pytest.mark.parametrize("m,d,k,b,storage", SHAPES)
+def test_backward_input_register_lists(orc, lds_form, m, d, k, b, storage):
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=200 + SHAPES.index((m, d, k, b, storage)))
+    print("bwi lds", m, d, k, b, storage, flush=True)
+    idx, W, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_g(cfg)
+    L = usl.Layer(m, d, k, b, storage)
+    d_idx, d_W, d_g = gu.dev(idx), gu.dev(W), gu.dev(g)
+    gx = gu.empty((b, d)).fill_(float("nan"))
+    L.backward_input(d_g, d_idx, d_W, gx, b)
+    ref = orc.backward_input(g, idx, W, d)
+    assert_close(gu.host(gx), ref, 1e-4, "grad_x")
+    # a second call reuses the lists; a smaller batch leaves the other rows alone
+    gx.fill_(float("nan"))
+    nb = max(1, b // 2)
+    L.backward_input(d_g, d_idx, d_W, gx, nb)
+    got = gu.host(gx)
+    assert_close(got[:nb], ref[:nb], 1e-4, "grad_x, second call")
+    assert np.isnan(got[nb:]).all()
+    np.testing.assert_array_equal(gu.host(d_idx), idx)
+    L.check()
+    L.close()
+
+
+@pytest.mark.parametrize("pattern", ["two_features", "half_skewed"])
+def test_lists_longer_than_the_registers(orc, lds_form, pattern):
+    """Connectivity far from uniform: lists that do not fit a lane's registers go through the overflow list (its
+    part held in LDS and the part read from memory)."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    m, d, k, b = 40000, 2048, 2, 3
+    cfg = wl.custom(m, d, k, b, positives=3, index=230)
+    idx, W, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_g(cfg)
+    if pattern == "two_features":
+        idx[:, 0], idx[:, 1] = 7, 2040
+    else:                      # every second label into a handful of features, the rest uniform
+        idx[::2, 0] = (np.arange(0, m, 2) % 5) * 400 + 3
+        idx[::2, 1] = (np.arange(0, m, 2) % 5) * 400 + 4
+    L = usl.Layer(m, d, k, b)
+    gx = gu.empty((b, d)).fill_(float("nan"))
+    L.backward_input(gu.dev(g), gu.dev(idx), gu.dev(W), gx, b)
+    assert_close(gu.host(gx), orc.backward_input(g, idx, W, d), 1e-4, "grad_x")
+    L.close()
+
+
+def test_changed_idx_is_noticed(orc, lds_form):
+    """Contents of idx replaced at the same address without usl_invalidate: NaN and USL_ESTALE, then right again."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    m, d, k, b = 70000, 2048, 2, 4
+    cfg = wl.custom(m, d, k, b, positives=3, index=240)
+    idx1, W, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_g(cfg)
+    idx2 = wl.gen_idx(wl.custom(m, d, k, b, index=241))
+    L = usl.Layer(m, d, k, b)
+    d_idx, d_W, d_g, gx = gu.dev(idx1), gu.dev(W), gu.dev(g), gu.empty((b, d))
+    L.backward_input(d_g, d_idx, d_W, gx, b)
+    assert_close(gu.host(gx), orc.backward_input(g, idx1, W, d), 1e-4, "grad_x, first idx")
+    d_idx.copy_(torch.from_numpy(idx2))
+    rc = usl._lib.usl_backward_input(L._h, d_g.data_ptr(), d_idx.data_ptr(), d_W.data_ptr(), gx.data_ptr(), b)
+    assert rc == usl.USL_OK
+    assert torch.isnan(gx).all()
+    with pytest.raises(usl.UslError) as e:
+        L.check()
+    assert e.value.status == usl.USL_ESTALE
+    rc = usl._lib.usl_backward_input(L._h, d_g.data_ptr(), d_idx.data_ptr(), d_W.data_ptr(), gx.data_ptr(), b)
+    assert rc == usl.USL_OK
+    assert_close(gu.host(gx), orc.backward_input(g, idx2, W, d), 1e-4, "grad_x after the check invalidated the lists")
+    L.check()
+    L.close()
+
+
+@pytest.mark.parametrize("loss_kind,storage,easy", [(0, "f32", False), (1, "bf16", False), (1, "f32", True)])
+def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy, monkeypatch):
+    """The fused step where the input gradient takes this form: loss row-major, then the products."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    if easy:
+        monkeypatch.setenv("USL_TUNE_SPARSE", "always")
+    m, d, k, b = 70000, 2048, 2, 9
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=250 + loss_kind)
+    hp = wl.ADAM
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    if easy:
+        W = wl.store(-np.abs(wl.as_f32(W)) * 8.0 - 0.5, storage)
+    off, lab = wl.gen_targets(cfg)
+    r = wl.rng(cfg, 5)
+    m1 = (r.standard_normal((m, k)) * 1e-3).astype(np.float32)
+    m2 = (r.random((m, k)) * 1e-6).astype(np.float32)
+    scale, t = float(np.float32(1.0 / b)), 2
+    L = usl.Layer(m, d, k, b, storage)
+    d_idx, d_W, d_x, d_m1, d_m2 = gu.dev(idx), gu.dev(W), gu.dev(x), gu.dev(m1), gu.dev(m2)
+    g, gW, gx, loss = gu.empty((b, m)), gu.empty((m, k)), gu.empty((b, d)).fill_(float("nan")), gu.empty((1,))
+    L.train_step(d_x, d_idx, d_W, d_m1, d_m2, gu.dev(off), gu.dev(lab), loss_kind, scale, t,
+                 hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], g, gW, gx, loss, b)
+    out = orc.forward(x, idx, W)
+    ref_loss, ref_g = (orc.bce_loss_grad if loss_kind == 0 else orc.sqh_loss_grad)(out, off, lab, scale)
+    got_g = gu.host(g)
+    assert_close(got_g, ref_g, 1e-5, "g")
+    assert abs(float(loss.item()) - ref_loss) <= 1e-5 * abs(ref_loss)
+    got_gW = gu.host(gW)
+    assert_close(got_gW, orc.backward_weight(got_g, x, idx), 1e-5, "grad_W")
+    assert_close(gu.host(gx), orc.backward_input(got_g, idx, W, d), 1e-4, "grad_x")
+    m1r, m2r, W2 = m1.copy(), m2.copy(), W.copy()
+    orc.adam_step(W2, got_gW, m1r, m2r, t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"])
+    assert_close(gu.host(d_m1), m1r, 1e-4, "m1")
+    assert_close(gu.host(d_m2), m2r, 1e-4, "m2")
+    L.check()
+    L.close()
