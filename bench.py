@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 5669860147, "forward": 924948889, "backward_weight": 940677529},
+    "large": {"backward_input": 2832098918, "forward": 924948889, "backward_weight": 940782387},
     "large_wide": {"backward_input": 17072390144, "forward": 2478204518, "backward_weight": 2652372992},
     "stress": {"backward_input": 204285778329, "forward": 26036771225, "backward_weight": 26131772211},
 }
@@ -34,6 +34,8 @@ KERNELS_OF_CALL = {
     "backward_weight": "k_backward_weight (1 launch)",
     "backward_input": "a look at a sample of g, k_gather_w, then per group of 256 instances k_transpose_g + one "
                       "k_bwd_input_window per window of 24576 labels + k_untile",
+    "backward_input_register_lists": "a look at a sample of g, k_idx_fingerprint, then per group of 256 instances "
+                                     "k_bwi_lds (lists in registers, rows of g through LDS) + k_lf_reduce",
     "adam": "k_adam (1 launch)",
 }
 
@@ -53,11 +55,20 @@ def algorithmic_bytes(cfg):
     return per
 
 
+def register_list_form(cfg):
+    """Whether usl_backward_input takes its register-list form for this shape (the library's rule: about 32
+    connections per window of 32768 labels and feature, whole blocks of 2048 features, enough workgroups)."""
+    return (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 32768 * cfg.k == 32 * cfg.d
+            and -(-cfg.m // 32768) * (cfg.d // 2048) * 4 >= 256 * 3)
+
+
 def launches_in_call(cfg, call):
     """Kernel launches behind one call (the HIP-event time of the call covers all of them)."""
     if call != "backward_input":
         return 2 if call == "bce" else 1
     groups = -(-cfg.b // 256)
+    if register_list_form(cfg):
+        return 3 + groups * 2
     win = int((24576.0 * ((cfg.d / 32768.0) * (32.0 / cfg.k)) ** 0.5 + 2048.0) / 4096.0) * 4096   # labels per window,
     win = min(max(win, 16384), 49152)                                                              # as the library picks them
     return 3 + groups * (1 + -(-cfg.m // win) + 1 + 1)
@@ -300,7 +311,8 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom)
     if args.traffic_kib is not None:
         traffic = args.traffic_kib * 1024
-    roof = {"bound": "hbm", "kernel": "usl_%s: %s" % (dom, KERNELS_OF_CALL[dom]),
+    dom_kernels = KERNELS_OF_CALL["backward_input_register_lists" if dom == "backward_input" and register_list_form(cfg) else dom]
+    roof = {"bound": "hbm", "kernel": "usl_%s: %s" % (dom, dom_kernels),
             "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
             "ms_per_launch": round(call_ms[dom], 4), "launches_in_call": launches_in_call(cfg, dom),

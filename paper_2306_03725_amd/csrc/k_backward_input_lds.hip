@@ -72,22 +72,24 @@ k_lf_count(const int32_t* __restrict__ idx, int64_t m, int k, int d, int splits,
 
 // One workgroup per (window, feature block): ranks the block's NF features by list length, pairs them, fixes the
 // slot ranges of every wavefront and counts what will not fit.
-//   where[w][c]   = lane | zone << 10 | cap << 16   (zone 0 = list A, 1 = list B; cap = slots the list may use)
 //   feat[wg][z][lane] = feature (within the block) whose list lane holds in zone z
 //   caps[wg][wave]    = acap | bcap << 8
-//   ov_count[wg]      = entries beyond the caps; they are kept list by list:
-//   count[w][c]       becomes where the overflow of feature c starts in the workgroup's overflow list
+//   where[w][c]       = where the list of feature c starts among the workgroup's entries (k_lf_fill puts them there)
+//   n_ent[wg]         = entries of the workgroup
+//   ov_off[w][c]      = where what does not fit of that list starts in the workgroup's overflow list
+//   n_ov[wg]          = entries beyond the allowances
 //   ovr[wg][z][lane]  = start | n << 16: the part of that list's overflow among the first NT entries (those the
 //                       gather kernel keeps in LDS and the list's own lane adds up)
 __global__ void __launch_bounds__(NT)
-k_lf_plan(uint32_t* __restrict__ count, int d, int nfb, uint32_t* __restrict__ where, uint16_t* __restrict__ feat,
-          uint32_t* __restrict__ caps, uint32_t* __restrict__ ov_count, uint32_t* __restrict__ ovr) {
+k_lf_plan(const uint32_t* __restrict__ count, int d, int nfb, uint32_t* __restrict__ where, uint32_t* __restrict__ ov_off,
+          uint16_t* __restrict__ feat, uint32_t* __restrict__ caps, uint32_t* __restrict__ n_ent,
+          uint32_t* __restrict__ n_ov, uint32_t* __restrict__ ovr) {
     __shared__ uint32_t start[256];
     __shared__ uint32_t scan[NT];
     __shared__ uint16_t len_of[2][NT];
     __shared__ uint32_t cap_of[NT / 64];
     const int wg = blockIdx.x, w = wg / nfb, fb = wg % nfb;
-    uint32_t* cnt = count + (size_t)w * d + (size_t)fb * NF;
+    const uint32_t* cnt = count + (size_t)w * d + (size_t)fb * NF;
     if (threadIdx.x < 256) start[threadIdx.x] = 0;
     __syncthreads();
     uint32_t n[2];
@@ -146,29 +148,42 @@ k_lf_plan(uint32_t* __restrict__ count, int d, int nfb, uint32_t* __restrict__ w
     for (int q = 0; q < 2; ++q) {
         const uint32_t cw = cap_of[lane_of[q] >> 6];
         const uint32_t cap = zone_of[q] == 0 ? (cw & 0xFFu) : (cw >> 8);
-        where[(size_t)w * d + (size_t)fb * NF + threadIdx.x + q * NT] = lane_of[q] | (zone_of[q] << 10) | (cap << 16);
         ov[q] = n[q] > cap ? n[q] - cap : 0u;
     }
-    scan[threadIdx.x] = ov[0] + ov[1];
-    __syncthreads();
-    for (int o = 1; o < NT; o <<= 1) {
-        const uint32_t t = threadIdx.x >= (unsigned)o ? scan[threadIdx.x - o] : 0u;
+    auto block_scan = [&](uint32_t mine) -> uint32_t {   // inclusive, over the lanes of the workgroup
         __syncthreads();
-        scan[threadIdx.x] += t;
+        scan[threadIdx.x] = mine;
         __syncthreads();
+        for (int o = 1; o < NT; o <<= 1) {
+            const uint32_t t = threadIdx.x >= (unsigned)o ? scan[threadIdx.x - o] : 0u;
+            __syncthreads();
+            scan[threadIdx.x] += t;
+            __syncthreads();
+        }
+        return scan[threadIdx.x];
+    };
+    const size_t bin = (size_t)w * d + (size_t)fb * NF + threadIdx.x;
+    {
+        const uint32_t incl = block_scan(n[0] + n[1]);
+        where[bin] = incl - n[0] - n[1];
+        where[bin + NT] = incl - n[1];
+        if (threadIdx.x == NT - 1) n_ent[wg] = incl;
     }
-    uint32_t at = scan[threadIdx.x] - ov[0] - ov[1];
+    {
+        const uint32_t incl = block_scan(ov[0] + ov[1]);
+        uint32_t at = incl - ov[0] - ov[1];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        cnt[threadIdx.x + q * NT] = at;
-        const uint32_t first = min(at, (uint32_t)NT);
-        ovr[((size_t)wg * 2 + zone_of[q]) * NT + lane_of[q]] = first | (min(ov[q], (uint32_t)NT - first) << 16);
-        at += ov[q];
+        for (int q = 0; q < 2; ++q) {
+            ov_off[bin + q * NT] = at;
+            const uint32_t first = min(at, (uint32_t)NT);
+            ovr[((size_t)wg * 2 + zone_of[q]) * NT + lane_of[q]] = first | (min(ov[q], (uint32_t)NT - first) << 16);
+            at += ov[q];
+        }
+        if (threadIdx.x == NT - 1) n_ov[wg] = incl;
     }
-    if (threadIdx.x == NT - 1) ov_count[wg] = scan[NT - 1];
 }
 
-// ov_base[wg] = overflow entries of the workgroups before wg; ov_base[nwg] = all of them (one block).
+// ov_base[wg] = sum of ov_count over the workgroups before wg; ov_base[nwg] = all of them (one block).
 __global__ void __launch_bounds__(1024)
 k_lf_scan(const uint32_t* __restrict__ ov_count, int nwg, uint32_t* __restrict__ ov_base) {
     __shared__ uint32_t part[1024];
@@ -189,15 +204,14 @@ k_lf_scan(const uint32_t* __restrict__ ov_count, int nwg, uint32_t* __restrict__
     if (threadIdx.x == 1023) ov_base[nwg] = part[1023];
 }
 
-// Places every connection: slot p of its list (p by a cursor: the order inside a list is not fixed) goes to register
-// slot p (list A) or KTOT-1-p (list B) of its lane, or to its list's part of the workgroup's overflow list.  Same decomposition as
-// k_lf_count: a share's positions in every list are reserved with one global atomic per feature, then handed out
-// from LDS cursors.
+// Groups the connections by (workgroup of the gather kernel, feature): ent[ent_base[wg] + where[w][c] + p] = flat
+// slot j*k+t of the p-th connection from window w into feature c (p by a cursor: the order inside a list is not
+// fixed).  Same decomposition as k_lf_count: a share's positions in every list are reserved with one global atomic
+// per feature, then handed out from LDS cursors.
 struct OvEntry { uint16_t feature; uint16_t label; uint32_t slot; };
 __global__ void __launch_bounds__(NT)
 k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int nfb, int splits, const uint32_t* __restrict__ where,
-          uint32_t* __restrict__ taken, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot,
-          const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, OvEntry* __restrict__ ov) {
+          uint32_t* __restrict__ taken, const uint32_t* __restrict__ ent_base, uint32_t* __restrict__ ent) {
     extern __shared__ uint32_t cur[];
     const int c0 = blockIdx.y * CHUNK, nc = min(CHUNK, d - c0);
     const int w = blockIdx.x / splits;
@@ -211,30 +225,14 @@ k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int nfb, int
     }
     __syncthreads();
     const size_t bin0 = (size_t)w * d + c0;
-    for (int q = threadIdx.x; q < nc; q += NT) {
+    for (int q = threadIdx.x; q < nc; q += NT) {   // from here cur[q] = where this share's part of the list starts
         const uint32_t n = cur[q];
-        if (n) cur[q] = atomicAdd(&taken[bin0 + q], n);
+        if (n) cur[q] = atomicAdd(&taken[bin0 + q], n) + where[bin0 + q] + ent_base[(size_t)w * nfb + (c0 + q) / NF];
     }
     __syncthreads();
     for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
         const uint32_t c = (uint32_t)(idx[e] - c0);
-        if (c >= (uint32_t)nc) continue;
-        const uint32_t p = atomicAdd(&cur[c], 1u);
-        const uint32_t info = where[bin0 + c];
-        const uint32_t lane = info & 1023u, zone = (info >> 10) & 1u, cap = info >> 16;
-        const int col = c0 + (int)c;
-        const size_t wg = (size_t)w * nfb + col / NF;
-        const uint16_t lab16 = (uint16_t)((int64_t)(e / (size_t)k) - (int64_t)w * WL);
-        if (p < cap) {
-            const uint32_t t = zone == 0 ? p : (uint32_t)(KTOT - 1) - p;
-            const size_t at = (wg * KTOT + t) * NT + lane;
-            lab[at] = lab16;
-            slot[at] = (uint32_t)e;
-        } else {
-            OvEntry o;
-            o.feature = (uint16_t)(col % NF); o.label = lab16; o.slot = (uint32_t)e;
-            ov[(size_t)ov_base[wg] + ov_off[bin0 + c] + (p - cap)] = o;
-        }
+        if (c < (uint32_t)nc) ent[atomicAdd(&cur[c], 1u)] = (uint32_t)e;
     }
 }
 
@@ -248,14 +246,16 @@ k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int nfb, int
 // empty places, which may go to any step and read any bank.  A lane that finds no bank among its entries spends an
 // empty place (reading a label whose bank is free: with a zero weight) while it has one.
 // One half-wavefront per (workgroup of the gather kernel, zone, 32 lanes); lane i is list i and also bank i.
-// Reads the lists as filled (lab0 / slot0), writes them ordered (lab / slot).  Any outcome is a valid order: it
-// changes speed, never results.
+// Reads the lists as k_lf_fill grouped them (ent), writes them ordered into the places the gather kernel loads its
+// registers from (lab / slot: [workgroup][slot][lane]) and what exceeds the allowance into the overflow list.  Any
+// outcome is a valid order: it changes speed, never results.  rounds = 0: the lists stay in the order of ent.
 constexpr int SG = 8;   // half-wavefronts per workgroup
 __global__ void __launch_bounds__(SG * 32)
-k_lf_schedule(const uint16_t* __restrict__ lab0, const uint32_t* __restrict__ slot0, const uint32_t* __restrict__ caps,
-              int64_t m, int nfb, int rounds, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot) {
-    __shared__ uint8_t slots[SG][32][KTOT + 4];   // first the bank of every entry, then my entries sorted by bank
-    __shared__ uint8_t ord[SG][32][KTOT + 4];     // entry read at step s (0x80 | bank: an empty place)
+k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent_base, const uint32_t* __restrict__ where,
+              const uint32_t* __restrict__ count, const uint16_t* __restrict__ feat, const uint32_t* __restrict__ caps,
+              const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, int64_t m, int k, int d, int nfb,
+              int rounds, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot, OvEntry* __restrict__ ov) {
+    __shared__ uint8_t slots[SG][32][KTOT + 4];   // my entries sorted by bank
     __shared__ uint8_t left_in[SG][32][36];       // entries of mine not placed yet, per bank
     __shared__ uint8_t end_of[SG][32][36];        // where bank b's entries end in the sorted list
     __shared__ int deg0[SG][32];
@@ -267,32 +267,45 @@ k_lf_schedule(const uint16_t* __restrict__ lab0, const uint32_t* __restrict__ sl
     const int zone = (int)(gid >> 5) & 1, half = (int)gid & 31;   // the two halves of a wavefront are neighbours: same allowance
     const uint32_t cw = caps[wg * (NT / 64) + (half >> 1)];
     const int cap = zone ? (int)(cw >> 8) : (int)(cw & 0xFFu);
-    const int w = (int)(wg / nfb);
+    const int w = (int)(wg / nfb), fb = (int)(wg % nfb);
     const bool wide = m - (int64_t)w * WL >= 32;   // the window has a label for every bank
     auto at = [&](int p) -> size_t { return (wg * KTOT + (zone ? KTOT - 1 - p : p)) * NT + half * 32 + lane; };
+    // my list: feature, length, where its entries are; label of an entry = its flat slot / k, counted from the window's first
+    const uint32_t f = feat[(wg * 2 + zone) * NT + half * 32 + lane];
+    const size_t bin = (size_t)w * d + (size_t)fb * NF + f;
+    const uint32_t len = count[bin];
+    const uint32_t* my = ent + ent_base[wg] + where[bin];
+    auto label_of = [&](uint32_t e) -> uint32_t { return e / (uint32_t)k - (uint32_t)w * (uint32_t)WL; };
+    const int n = (int)min(len, (uint32_t)cap);     // entries that get a register slot
+    for (uint32_t p = (uint32_t)cap; p < len; ++p) {   // the others: to the list's part of the overflow list
+        OvEntry o;
+        o.feature = (uint16_t)f; o.label = (uint16_t)label_of(my[p]); o.slot = my[p];
+        ov[(size_t)ov_base[wg] + ov_off[bin] + (p - (uint32_t)cap)] = o;
+    }
+    if (rounds <= 0) {
+        for (int s = 0; s < cap; ++s) {
+            lab[at(s)] = s < n ? (uint16_t)label_of(my[s]) : (uint16_t)0;
+            slot[at(s)] = s < n ? my[s] : PAD_SLOT;
+        }
+        return;   // the whole wavefront: rounds is the same for all
+    }
     deg0[gl][lane] = 0;
     for (int b = 0; b < 32; ++b) left_in[gl][lane][b] = 0;
     __syncthreads();
     uint8_t* mine = slots[gl][lane];
     uint8_t* cnt = left_in[gl][lane];
     uint8_t* ends = end_of[gl][lane];
-    int n = 0;                     // entries of my list (they sit in its first places)
-    for (int p = 0; p < cap; ++p) {
-        if (slot0[at(p)] == PAD_SLOT) break;
-        const int b = lab0[at(p)] & 31;
-        mine[p] = (uint8_t)b;
+    for (int p = 0; p < n; ++p) {
+        const int b = (int)(label_of(my[p]) & 31u);
         ++cnt[b];
         atomicAdd(&deg0[gl][b], 1);
-        n = p + 1;
     }
     int wild = cap - n;            // empty places left
     uint32_t avail = 0;            // banks my unplaced entries read
-    {   // counting sort of my entries by bank, in place through ord (free until the first step)
+    {   // counting sort of my entries by bank (their banks are read a second time: no room to keep them)
         int run = 0;
         for (int b = 0; b < 32; ++b) { run += cnt[b]; ends[b] = (uint8_t)run; if (cnt[b]) avail |= 1u << b; }
-        uint8_t* tmp = ord[gl][lane];
-        for (int p = 0; p < n; ++p) tmp[p] = mine[p];
-        for (int p = n - 1; p >= 0; --p) { const int b = tmp[p]; ends[b] = (uint8_t)(ends[b] - 1); mine[ends[b]] = (uint8_t)p; }
+        for (int p = n - 1; p >= 0; --p) { const int b = (int)(label_of(my[p]) & 31u); ends[b] = (uint8_t)(ends[b] - 1); mine[ends[b]] = (uint8_t)p; }
         for (int b = 0; b < 32; ++b) ends[b] = (uint8_t)(ends[b] + cnt[b]);   // back from starts to ends
     }
     __syncthreads();
@@ -382,20 +395,16 @@ k_lf_schedule(const uint16_t* __restrict__ lab0, const uint32_t* __restrict__ sl
                 if (lane == bb) ++myload;
             }
         }
-        if (wb >= 0) {
-            ord[gl][lane][s] = (uint8_t)(0x80 | wb);
+        if (wb >= 0) {             // an empty place: a label of the free bank, no weight
+            lab[at(s)] = (uint16_t)(wide ? wb : 0);
+            slot[at(s)] = PAD_SLOT;
         } else {                   // my next unplaced entry in that bank
             const int pick = mine[ends[mb] - cnt[mb]];
             if (--cnt[mb] == 0) avail &= ~(1u << mb);
-            ord[gl][lane][s] = (uint8_t)pick;
+            lab[at(s)] = (uint16_t)label_of(my[pick]);
+            slot[at(s)] = my[pick];
         }
         mydeg -= myload;
-    }
-    for (int s = 0; s < cap; ++s) {
-        const int o = ord[gl][lane][s];
-        const bool empty = (o & 0x80) != 0;
-        lab[at(s)] = empty ? (uint16_t)(wide ? (o & 31) : 0) : lab0[at(o)];
-        slot[at(s)] = empty ? PAD_SLOT : slot0[at(o)];
     }
 }
 
@@ -519,15 +528,19 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
         if (i + 1 < rows && warms)   // the window's workgroups share the warm-up of the next row slice, one load per 128-byte line
             asm volatile("global_load_dword %0, %1, %2" : "=v"(token) : "v"((uint32_t)(fb * per + (int)threadIdx.x) * 128u), "s"(grow + (size_t)m * 4));
         float acc_a = 0.f, acc_b = 0.f;
+        // compared afresh in every pass (one scalar compare per group): kept across the loop, the 34 outcomes would
+        // each take a pair of scalar registers, more than there are
+        int ac = acap, bc = bcap;
+        asm volatile("" : "+s"(ac), "+s"(bc));
 #pragma unroll
         for (int q = 0; q < KTOT / 4; ++q) {
-            if (q * 4 < acap) {
+            if (q * 4 < ac) {
                 gather4(acc_a, pk[q * 2], pk[q * 2 + 1], wt[q * 4], wt[q * 4 + 1], wt[q * 4 + 2], wt[q * 4 + 3]);
             }
         }
 #pragma unroll
         for (int q = 0; q < KTOT / 4; ++q) {
-            if (q * 4 >= KTOT - bcap) {
+            if (q * 4 >= KTOT - bc) {
                 gather4(acc_b, pk[q * 2], pk[q * 2 + 1], wt[q * 4], wt[q * 4 + 1], wt[q * 4 + 2], wt[q * 4 + 3]);
             }
         }
@@ -603,23 +616,19 @@ static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     USL_TRY(usl_reserve(c, (void**)&c->lf_where, &c->lf_where_cap, nbins * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_feat, &c->lf_feat_cap, (size_t)nwg * 2 * NT * 2));
     USL_TRY(usl_reserve(c, (void**)&c->lf_caps, &c->lf_caps_cap, (size_t)nwg * (NT / 64) * 4));
-    USL_TRY(usl_reserve(c, (void**)&c->lf_ov_base, &c->lf_ov_base_cap, ((size_t)nwg * 2 + 1) * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ov_base, &c->lf_ov_base_cap, ((size_t)nwg * 4 + 2) * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_ovr, &c->lf_ovr_cap, (size_t)nwg * 2 * NT * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_lab, &c->lf_lab_cap, (size_t)nwg * KTOT * NT * 2));
     USL_TRY(usl_reserve(c, (void**)&c->lf_slot, &c->lf_slot_cap, (size_t)nwg * KTOT * NT * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ent, &c->lf_ent_cap, N * 4));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ovoff, &c->lf_ovoff_cap, nbins * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_ov, &c->lf_ov_cap, N * sizeof(OvEntry)));
     int rounds = 3;                // of proposals per step of the bank-aware order; 0 = lists stay as filled
     if (const char* e = getenv("USL_TUNE_ROUNDS")) rounds = atoi(e);
-    uint16_t* lab0 = c->lf_lab;
-    uint32_t* slot0 = c->lf_slot;
-    if (rounds > 0) {
-        USL_TRY(usl_reserve(c, (void**)&c->lf_lab0, &c->lf_lab0_cap, (size_t)nwg * KTOT * NT * 2));
-        USL_TRY(usl_reserve(c, (void**)&c->lf_slot0, &c->lf_slot0_cap, (size_t)nwg * KTOT * NT * 4));
-        lab0 = c->lf_lab0;
-        slot0 = c->lf_slot0;
-    }
-    uint32_t* ov_base = c->lf_ov_base;
-    uint32_t* ov_count = c->lf_ov_base + nwg + 1;
+    uint32_t* ov_base = c->lf_ov_base;               // [nwg + 1]
+    uint32_t* n_ov = ov_base + nwg + 1;              // [nwg]
+    uint32_t* ent_base = n_ov + nwg;                 // [nwg + 1]
+    uint32_t* n_ent = ent_base + nwg + 1;            // [nwg]
     const unsigned chunks = (unsigned)((c->d + CHUNK - 1) / CHUNK);
     int splits = (int)((size_t)c->num_cu / ((size_t)nwin * chunks));
     splits = splits < 1 ? 1 : splits > 16 ? 16 : splits;
@@ -630,17 +639,16 @@ static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     const dim3 fillg(c->num_cu * 4), fillb(256);
     hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_count, nbins, 0u);
     hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_taken, nbins, 0u);
-    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, slot0, (size_t)nwg * KTOT * NT, PAD_SLOT);
-    hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, reinterpret_cast<uint32_t*>(lab0), (size_t)nwg * KTOT * NT / 2, 0u);
     hipLaunchKernelGGL(k_lf_count, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, splits, c->lf_count);
-    hipLaunchKernelGGL(k_lf_plan, dim3((unsigned)nwg), dim3(NT), 0, c->stream, c->lf_count, c->d, nfb, c->lf_where, c->lf_feat,
-                       c->lf_caps, ov_count, c->lf_ovr);
-    hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, ov_count, nwg, ov_base);
+    hipLaunchKernelGGL(k_lf_plan, dim3((unsigned)nwg), dim3(NT), 0, c->stream, c->lf_count, c->d, nfb, c->lf_where, c->lf_ovoff,
+                       c->lf_feat, c->lf_caps, n_ent, n_ov, c->lf_ovr);
+    hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, n_ov, nwg, ov_base);
+    hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, n_ent, nwg, ent_base);
     hipLaunchKernelGGL(k_lf_fill, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, nfb, splits, c->lf_where, c->lf_taken,
-                       lab0, slot0, ov_base, c->lf_count, reinterpret_cast<OvEntry*>(c->lf_ov));
-    if (rounds > 0)
-        hipLaunchKernelGGL(k_lf_schedule, dim3((unsigned)(nwg * 64 / SG)), dim3(SG * 32), 0, c->stream, lab0, slot0, c->lf_caps,
-                           c->m, nfb, rounds, c->lf_lab, c->lf_slot);
+                       ent_base, c->lf_ent);
+    hipLaunchKernelGGL(k_lf_schedule, dim3((unsigned)(nwg * 64 / SG)), dim3(SG * 32), 0, c->stream, c->lf_ent, ent_base,
+                       c->lf_where, c->lf_count, c->lf_feat, c->lf_caps, ov_base, c->lf_ovoff, c->m, c->k, c->d, nfb, rounds,
+                       c->lf_lab, c->lf_slot, reinterpret_cast<OvEntry*>(c->lf_ov));
     USL_TRY(usl_idx_fingerprint(c, idx, 1));
     USL_TRY(usl_check_launch(c, "register lists of the input gradient"));
     c->lf_built_for = idx;

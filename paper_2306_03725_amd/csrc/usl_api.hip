@@ -34,7 +34,7 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
                         c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part,
                         c->nz_state, c->nz_lab, c->nz_val, c->idx_print,
-                        c->lf_count, c->lf_taken, c->lf_where, c->lf_feat, c->lf_caps, c->lf_ov_base, c->lf_ovr, c->lf_lab, c->lf_lab0, c->lf_slot0,
+                        c->lf_count, c->lf_taken, c->lf_where, c->lf_feat, c->lf_caps, c->lf_ov_base, c->lf_ovr, c->lf_lab, c->lf_ent, c->lf_ovoff,
                         c->lf_slot, c->lf_ov, c->lf_partial};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)

@@ -61,17 +61,17 @@ struct usl_ctx {
     int sparse_streak;        // looks in a row that found the sample sparse
     // the input gradient's feature-stationary form (k_backward_input_lds.hip): per (label window, feature block)
     // workgroup the register lists of its lanes, their plan, what did not fit, and the windows' partial sums
-    uint32_t* lf_count;       size_t lf_count_cap;    // [nwin*d] list lengths, then where a list's overflow starts
+    uint32_t* lf_count;       size_t lf_count_cap;    // [nwin*d] list lengths
     uint32_t* lf_taken;       size_t lf_taken_cap;    // [nwin*d] positions handed out while filling
-    uint32_t* lf_where;       size_t lf_where_cap;    // [nwin*d] lane, zone and slot allowance of a feature's list
+    uint32_t* lf_where;       size_t lf_where_cap;    // [nwin*d] where a feature's list starts among its workgroup's entries
     uint16_t* lf_feat;        size_t lf_feat_cap;     // [wg][2][1024] feature of a lane's list
     uint32_t* lf_caps;        size_t lf_caps_cap;     // [wg][16] slots the wavefronts visit
-    uint32_t* lf_ov_base;     size_t lf_ov_base_cap;  // [wg+1] start of a workgroup's overflow entries, then [wg] their number
+    uint32_t* lf_ov_base;     size_t lf_ov_base_cap;  // [wg+1] start of a workgroup's overflow entries, [wg] their number; the same two for all its entries
     uint32_t* lf_ovr;         size_t lf_ovr_cap;      // [wg][2][1024] a lane's lists' share of the overflow entries held in LDS
     uint16_t* lf_lab;         size_t lf_lab_cap;      // [wg][slots][1024] label within the window
     uint32_t* lf_slot;        size_t lf_slot_cap;     // [wg][slots][1024] flat slot j*k+t (where the weight lives)
-    uint16_t* lf_lab0;        size_t lf_lab0_cap;     // the same two as filled, before the bank-aware order
-    uint32_t* lf_slot0;       size_t lf_slot0_cap;
+    uint32_t* lf_ent;         size_t lf_ent_cap;      // [m*k] flat slots grouped by (workgroup, feature), before the bank-aware order
+    uint32_t* lf_ovoff;       size_t lf_ovoff_cap;    // [nwin*d] where a list's overflow starts in its workgroup's
     void* lf_ov;              size_t lf_ov_cap;       // overflow entries
     float* lf_partial;        size_t lf_partial_cap;  // [nwin][rows of a pass][d]
     const int32_t* lf_built_for;                      // idx pointer the lists were built from (NULL = stale)

@@ -100,20 +100,32 @@ def test_changed_idx_is_noticed(orc, lds_form):
     L.close()
 
 
-@pytest.mark.parametrize("loss_kind,storage,easy", [(0, "f32", False), (1, "bf16", False), (1, "f32", True)])
-def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy, monkeypatch):
+# the last three: a layer large enough for the kernels of the large layers (float32, k = 32, one row of x per stage);
+# targets with an empty instance, a label listed twice and a dense instance
+@pytest.mark.parametrize("loss_kind,storage,easy,shape", [
+    (0, "f32", False, (70000, 2048, 2, 9)), (1, "bf16", False, (70000, 2048, 2, 9)), (1, "f32", True, (70000, 2048, 2, 9)),
+    (0, "f32", False, (270000, 32768, 32, 5)), (1, "f32", False, (270000, 32768, 32, 5)), (1, "f32", True, (270000, 32768, 32, 5))])
+def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy, shape, monkeypatch):
     """The fused step where the input gradient takes this form: loss row-major, then the products."""
     import gpu_util as gu
     from paper_2306_03725_amd import usl
     if easy:
         monkeypatch.setenv("USL_TUNE_SPARSE", "always")
-    m, d, k, b = 70000, 2048, 2, 9
+    m, d, k, b = shape
     cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=250 + loss_kind)
+    print("train_step lds", shape, loss_kind, storage, easy, flush=True)
     hp = wl.ADAM
     idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
     if easy:
         W = wl.store(-np.abs(wl.as_f32(W)) * 8.0 - 0.5, storage)
     off, lab = wl.gen_targets(cfg)
+    if m == 270000:
+        lists = [list(lab[off[i]:off[i + 1]]) for i in range(b)]
+        lists[0] = []
+        lists[1] = lists[1] + lists[1][:2] + [m - 1, 0, m - 1]
+        lists[2] = list(range(0, m, 1000))
+        off = np.cumsum([0] + [len(l) for l in lists]).astype(np.int64)
+        lab = np.array([v for l in lists for v in l], np.int32)
     r = wl.rng(cfg, 5)
     m1 = (r.standard_normal((m, k)) * 1e-3).astype(np.float32)
     m2 = (r.random((m, k)) * 1e-6).astype(np.float32)

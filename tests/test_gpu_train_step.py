@@ -22,6 +22,8 @@ CASES = [
     (400001, 4096, 32, 5, "f32", 1, True, True),       # large layer, squared hinge, easy negatives: the lists of nonzeros
     (400000, 4096, 64, 3, "bf16", 1, True, True),
     (400000, 70000, 16, 2, "f32", 1, True, True),      # ... with an input row wider than one LDS slice
+    (270000, 32768, 32, 4, "f32", 0, False, False),    # no input gradient, large float32 layer with one row of x per stage
+    (270001, 20000, 32, 3, "f32", 1, False, False),    # ... with m % 4 != 0 and a ragged last block of labels
 ]
 
 
