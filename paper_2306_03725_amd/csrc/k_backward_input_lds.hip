@@ -29,7 +29,8 @@
 
 namespace {
 
-constexpr int WL = 32768;      // labels per window: one float32 row of 128 KiB in LDS
+constexpr int WL = 32768;      // most labels a window has: one float32 row of 128 KiB in LDS.  A layer's windows are of equal
+                               // size wl <= WL (a multiple of 4), as few as WL allows: no short last window whose workgroups idle
 constexpr int NF = 2048;       // features per workgroup (two per lane)
 constexpr int NT = 1024;
 constexpr int KTOT = 68;       // list slots per lane, shared by its two lists (with the rest of the kernel: the 128 registers a lane has)
@@ -41,10 +42,10 @@ __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
 }
 
 // The slots of one window's labels, cut into `splits` contiguous shares.
-__device__ __forceinline__ void share_of(int64_t m, int k, int splits, size_t* e0, size_t* e1) {
+__device__ __forceinline__ void share_of(int64_t m, int k, int wl, int splits, size_t* e0, size_t* e1) {
     const int w = blockIdx.x / splits, s = blockIdx.x % splits;
-    const size_t w0 = (size_t)w * WL * k;
-    const size_t w1 = (size_t)min((int64_t)(w + 1) * WL, m) * k;
+    const size_t w0 = (size_t)w * wl * k;
+    const size_t w1 = (size_t)min((int64_t)(w + 1) * wl, m) * k;
     const size_t per = (w1 - w0 + splits - 1) / splits;
     *e0 = min(w0 + per * s, w1);
     *e1 = min(*e0 + per, w1);
@@ -53,11 +54,11 @@ __device__ __forceinline__ void share_of(int64_t m, int k, int splits, size_t* e
 // count[w][c] += connections of this workgroup's share that lead into feature c (LDS histogram, then one global
 // atomic per feature that occurs).  grid (nwin * splits, feature chunks).
 __global__ void __launch_bounds__(NT)
-k_lf_count(const int32_t* __restrict__ idx, int64_t m, int k, int d, int splits, uint32_t* __restrict__ count) {
+k_lf_count(const int32_t* __restrict__ idx, int64_t m, int k, int d, int wl, int splits, uint32_t* __restrict__ count) {
     extern __shared__ uint32_t hist[];
     const int c0 = blockIdx.y * CHUNK, nc = min(CHUNK, d - c0);
     size_t e0, e1;
-    share_of(m, k, splits, &e0, &e1);
+    share_of(m, k, wl, splits, &e0, &e1);
     for (int q = threadIdx.x; q < nc; q += NT) hist[q] = 0;
     __syncthreads();
     for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
@@ -210,13 +211,13 @@ k_lf_scan(const uint32_t* __restrict__ ov_count, int nwg, uint32_t* __restrict__
 // per feature, then handed out from LDS cursors.
 struct OvEntry { uint16_t feature; uint16_t label; uint32_t slot; };
 __global__ void __launch_bounds__(NT)
-k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int nfb, int splits, const uint32_t* __restrict__ where,
+k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int wl, int nfb, int splits, const uint32_t* __restrict__ where,
           uint32_t* __restrict__ taken, const uint32_t* __restrict__ ent_base, uint32_t* __restrict__ ent) {
     extern __shared__ uint32_t cur[];
     const int c0 = blockIdx.y * CHUNK, nc = min(CHUNK, d - c0);
     const int w = blockIdx.x / splits;
     size_t e0, e1;
-    share_of(m, k, splits, &e0, &e1);
+    share_of(m, k, wl, splits, &e0, &e1);
     for (int q = threadIdx.x; q < nc; q += NT) cur[q] = 0;
     __syncthreads();
     for (size_t e = e0 + threadIdx.x; e < e1; e += NT) {
@@ -253,7 +254,7 @@ constexpr int SG = 8;   // half-wavefronts per workgroup
 __global__ void __launch_bounds__(SG * 32)
 k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent_base, const uint32_t* __restrict__ where,
               const uint32_t* __restrict__ count, const uint16_t* __restrict__ feat, const uint32_t* __restrict__ caps,
-              const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, int64_t m, int k, int d, int nfb,
+              const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, int64_t m, int k, int d, int wl, int nfb,
               int rounds, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot, OvEntry* __restrict__ ov) {
     __shared__ uint8_t slots[SG][32][KTOT + 4];   // my entries sorted by bank
     __shared__ uint8_t left_in[SG][32][36];       // entries of mine not placed yet, per bank
@@ -268,14 +269,14 @@ k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent
     const uint32_t cw = caps[wg * (NT / 64) + (half >> 1)];
     const int cap = zone ? (int)(cw >> 8) : (int)(cw & 0xFFu);
     const int w = (int)(wg / nfb), fb = (int)(wg % nfb);
-    const bool wide = m - (int64_t)w * WL >= 32;   // the window has a label for every bank
+    const bool wide = m - (int64_t)w * wl >= 32;   // the window has a label for every bank
     auto at = [&](int p) -> size_t { return (wg * KTOT + (zone ? KTOT - 1 - p : p)) * NT + half * 32 + lane; };
     // my list: feature, length, where its entries are; label of an entry = its flat slot / k, counted from the window's first
     const uint32_t f = feat[(wg * 2 + zone) * NT + half * 32 + lane];
     const size_t bin = (size_t)w * d + (size_t)fb * NF + f;
     const uint32_t len = count[bin];
     const uint32_t* my = ent + ent_base[wg] + where[bin];
-    auto label_of = [&](uint32_t e) -> uint32_t { return e / (uint32_t)k - (uint32_t)w * (uint32_t)WL; };
+    auto label_of = [&](uint32_t e) -> uint32_t { return e / (uint32_t)k - (uint32_t)w * (uint32_t)wl; };
     const int n = (int)min(len, (uint32_t)cap);     // entries that get a register slot
     for (uint32_t p = (uint32_t)cap; p < len; ++p) {   // the others: to the list's part of the overflow list
         OvEntry o;
@@ -446,7 +447,7 @@ __device__ __forceinline__ void gather4(float& acc, uint32_t p0, uint32_t p1, fl
 // 2 * NT words: each lane's share of it.
 template <typename TS>
 __global__ void __launch_bounds__(NT)
-k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int k, int rows, int d, int nfb, int nwin,
+k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int k, int rows, int d, int wl, int nfb, int nwin,
           const uint16_t* __restrict__ lab, const uint32_t* __restrict__ slot, const uint16_t* __restrict__ feat,
           const uint32_t* __restrict__ caps, const uint32_t* __restrict__ ov_base, const OvEntry* __restrict__ ov,
           const uint32_t* __restrict__ ovr, float* __restrict__ partial, const uint32_t* __restrict__ gate) {
@@ -498,7 +499,7 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
     uint32_t* ovr_b = ovr_a + NT;
     ovr_a[threadIdx.x] = ovr[(wg * 2 + 0) * NT + threadIdx.x];
     ovr_b[threadIdx.x] = ovr[(wg * 2 + 1) * NT + threadIdx.x];
-    const int nl = (int)min((int64_t)WL, m - (int64_t)w * WL);   // labels of this window (the last one may be short)
+    const int nl = (int)min((int64_t)wl, m - (int64_t)w * wl);   // labels of this window (the last one may be short)
     const int nv = nl / 4, full = nv & ~63;                      // 16-byte pieces of a row slice; those in whole 1 KiB runs
     const int lines = (nl * 4 + 127) / 128, per = (lines + nfb - 1) / nfb;   // 128-byte lines; this workgroup's share of the warm-up
     const bool warms = (int)threadIdx.x < per && fb * per + (int)threadIdx.x < lines;
@@ -514,7 +515,7 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
     };
     uint32_t token = 0;   // receives the L2 warm-up loads; reserved until the next vmcnt(0) wait
     for (int i = 0; i < rows; ++i) {
-        const char* grow = reinterpret_cast<const char*>(g + (size_t)w * WL + (size_t)i * m);   // uniform
+        const char* grow = reinterpret_cast<const char*>(g + (size_t)w * wl + (size_t)i * m);   // uniform
         {   // the row slice: whole 1 KiB pieces by LDS-DMA, the ragged end through registers
             for (int v = (threadIdx.x >> 6) * 64; v < full; v += NT)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + ((uint32_t)v * 16u + (threadIdx.x & 63u) * 16u)),
@@ -592,24 +593,38 @@ k_lf_reduce(const float4* __restrict__ partial, int nwin, size_t n4, float4* __r
 
 }  // namespace
 
-// Is this layer one for the LDS form?  Lists of about 32 entries per (window, feature) -- WL*k == 32*d --, whole
-// feature blocks, 16-byte aligned rows of g, and enough (window, feature block) workgroups to fill the chip.
-// USL_TUNE_BWI=lds forces it where the shape allows at all, =l2 forbids it.
+// Windows: as many labels as send about 32 connections into a feature (the registers of a lane hold two such lists),
+// at most WL (the LDS row), a multiple of 4 (16-byte copies); a layer's windows are of equal size.
+static int lf_window_cap(const usl_ctx* c) {
+    const int64_t by_lists = (int64_t)32 * c->d / c->k;
+    return (int)((by_lists < WL ? by_lists : (int64_t)WL) / 4 * 4);
+}
+static int lf_windows(const usl_ctx* c) { const int cap = lf_window_cap(c); return (int)((c->m + cap - 1) / cap); }
+static int lf_window_labels(const usl_ctx* c) {
+    const int64_t nwin = lf_windows(c);
+    return (int)(((c->m + nwin - 1) / nwin + 3) / 4 * 4);
+}
+
+// Is this layer one for the LDS form?  Lists of about 32 entries per (window, feature) from windows of 16384 to
+// 32768 labels (k / d between 1/1024 and 1/512: longer windows do not fit LDS, with shorter ones the partial sums of
+// the many windows outweigh the gain), whole feature blocks, 16-byte aligned rows of g, and enough (window, feature
+// block) workgroups to fill the chip.  USL_TUNE_BWI=lds forces it where the shape allows at all, =l2 forbids it.
 bool usl_bwi_lds_applies(const usl_ctx* c) {
-    const bool shape_ok = c->d % NF == 0 && c->d <= 65536 && c->m % 4 == 0 && (int64_t)WL * c->k == (int64_t)32 * c->d &&
+    const int64_t lists32 = (int64_t)32 * c->d / c->k;   // labels that send 32 connections into a feature
+    const bool shape_ok = c->d % NF == 0 && c->d <= 65536 && c->m % 4 == 0 && lists32 >= 2048 && lists32 <= WL &&
                           c->m * (int64_t)c->k < (int64_t)PAD_SLOT;
     if (!shape_ok) return false;
     if (const char* e = getenv("USL_TUNE_BWI")) {
         if (!strcmp(e, "lds")) return true;
         if (!strcmp(e, "l2")) return false;
     }
-    const int64_t nwin = (c->m + WL - 1) / WL;
-    return nwin * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
+    const int64_t nwin = lf_windows(c);
+    return lists32 >= 16384 && nwin * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
 }
 
 static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     const size_t N = (size_t)c->m * c->k;
-    const int nwin = (int)((c->m + WL - 1) / WL), nfb = c->d / NF, nwg = nwin * nfb;
+    const int nwin = lf_windows(c), wl = lf_window_labels(c), nfb = c->d / NF, nwg = nwin * nfb;
     const size_t nbins = (size_t)nwin * c->d;
     USL_TRY(usl_reserve(c, (void**)&c->lf_count, &c->lf_count_cap, nbins * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_taken, &c->lf_taken_cap, nbins * 4));
@@ -639,15 +654,15 @@ static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     const dim3 fillg(c->num_cu * 4), fillb(256);
     hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_count, nbins, 0u);
     hipLaunchKernelGGL(k_fill_u32, fillg, fillb, 0, c->stream, c->lf_taken, nbins, 0u);
-    hipLaunchKernelGGL(k_lf_count, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, splits, c->lf_count);
+    hipLaunchKernelGGL(k_lf_count, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, wl, splits, c->lf_count);
     hipLaunchKernelGGL(k_lf_plan, dim3((unsigned)nwg), dim3(NT), 0, c->stream, c->lf_count, c->d, nfb, c->lf_where, c->lf_ovoff,
                        c->lf_feat, c->lf_caps, n_ent, n_ov, c->lf_ovr);
     hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, n_ov, nwg, ov_base);
     hipLaunchKernelGGL(k_lf_scan, dim3(1), dim3(1024), 0, c->stream, n_ent, nwg, ent_base);
-    hipLaunchKernelGGL(k_lf_fill, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, nfb, splits, c->lf_where, c->lf_taken,
+    hipLaunchKernelGGL(k_lf_fill, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, wl, nfb, splits, c->lf_where, c->lf_taken,
                        ent_base, c->lf_ent);
     hipLaunchKernelGGL(k_lf_schedule, dim3((unsigned)(nwg * 64 / SG)), dim3(SG * 32), 0, c->stream, c->lf_ent, ent_base,
-                       c->lf_where, c->lf_count, c->lf_feat, c->lf_caps, ov_base, c->lf_ovoff, c->m, c->k, c->d, nfb, rounds,
+                       c->lf_where, c->lf_count, c->lf_feat, c->lf_caps, ov_base, c->lf_ovoff, c->m, c->k, c->d, wl, nfb, rounds,
                        c->lf_lab, c->lf_slot, reinterpret_cast<OvEntry*>(c->lf_ov));
     USL_TRY(usl_idx_fingerprint(c, idx, 1));
     USL_TRY(usl_check_launch(c, "register lists of the input gradient"));
@@ -664,7 +679,7 @@ usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const
     if (c->lf_built_for != idx) USL_TRY(lf_build(c, idx));
     else USL_TRY(usl_idx_fingerprint(c, idx, 0));
     const uint32_t* stale = reinterpret_cast<const uint32_t*>(c->idx_print) + 4;
-    const int nwin = (int)((c->m + WL - 1) / WL), nfb = c->d / NF, nwg = nwin * nfb;
+    const int nwin = lf_windows(c), wl = lf_window_labels(c), nfb = c->d / NF, nwg = nwin * nfb;
     const int G = 256;   // instances per pass: the partial sums of one pass are nwin * G * d floats
     const int rows_max = c->max_b < G ? c->max_b : G;
     USL_TRY(usl_reserve(c, (void**)&c->lf_partial, &c->lf_partial_cap, (size_t)nwin * rows_max * c->d * 4));
@@ -688,7 +703,7 @@ usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const
                 checked[WHICH] = true;                                                                                   \
             }                                                                                                            \
             hipLaunchKernelGGL(k_bwi_lds<TS>, dim3(grid), dim3(NT), lds, c->stream, g + (size_t)i0 * c->m, (const TS*)W, \
-                               c->m, c->k, rows, c->d, nfb, nwin, c->lf_lab, c->lf_slot, c->lf_feat, c->lf_caps, ov_base,      \
+                               c->m, c->k, rows, c->d, wl, nfb, nwin, c->lf_lab, c->lf_slot, c->lf_feat, c->lf_caps, ov_base,      \
                                reinterpret_cast<const OvEntry*>(c->lf_ov), c->lf_ovr, c->lf_partial, gate);                         \
         } while (0)
         if (c->storage == USL_F32) USL_LDS_FORM(float, 0); else USL_LDS_FORM(uint16_t, 1);

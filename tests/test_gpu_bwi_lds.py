@@ -13,13 +13,15 @@ pytestmark = pytest.mark.gpu
 
 # (m, d, k, b, storage)
 SHAPES = [
-    (70000, 2048, 2, 5, "f32"),       # three windows, the last one short with a ragged end of 16-byte pieces
-    (32772, 2048, 2, 3, "f32"),       # a second window of four labels
+    (70000, 2048, 2, 5, "f32"),       # three windows of 23336 labels, the last one short with a ragged end of 16-byte pieces
+    (32772, 2048, 2, 3, "f32"),       # two windows of 16388 and 16384 labels
     (100000, 8192, 8, 37, "f32"),     # four feature blocks
     (40000, 32768, 32, 3, "f32"),     # the headline's d and k
     (40000, 32768, 32, 3, "bf16"),
     (66000, 65536, 64, 2, "bf16"),    # d of two histogram chunks
     (70000, 2048, 2, 300, "f32"),     # two passes over the batch (256 + 44 instances)
+    (20, 2048, 2, 1, "f32"),          # fewer labels than LDS banks, most lists empty, one instance
+    (131072, 4096, 4, 2, "bf16"),     # exactly four full windows
 ]
 
 
