@@ -599,7 +599,18 @@ static int lf_window_cap(const usl_ctx* c) {
     const int64_t by_lists = (int64_t)32 * c->d / c->k;
     return (int)((by_lists < WL ? by_lists : (int64_t)WL) / 4 * 4);
 }
-static int lf_windows(const usl_ctx* c) { const int cap = lf_window_cap(c); return (int)((c->m + cap - 1) / cap); }
+static int lf_windows(const usl_ctx* c) {
+    const int cap = lf_window_cap(c);
+    int64_t nwin = (c->m + cap - 1) / cap;
+    // (window, feature block) workgroups run in rounds of one per compute unit: a last round that is not full takes as
+    // long as a full one, so the windows are made a little shorter until the rounds are full (up to a quarter more
+    // windows: more than that and the extra partial sums cost what the shorter lists save)
+    const int64_t nfb = c->d / NF, cu = c->num_cu > 0 ? c->num_cu : 1;
+    const int64_t rounds = (nwin * nfb + cu - 1) / cu;
+    const int64_t full = rounds * cu / nfb;
+    if (full > nwin && full * 4 <= nwin * 5) nwin = full;
+    return (int)nwin;
+}
 static int lf_window_labels(const usl_ctx* c) {
     const int64_t nwin = lf_windows(c);
     return (int)(((c->m + nwin - 1) / nwin + 3) / 4 * 4);
@@ -680,8 +691,13 @@ usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const
     else USL_TRY(usl_idx_fingerprint(c, idx, 0));
     const uint32_t* stale = reinterpret_cast<const uint32_t*>(c->idx_print) + 4;
     const int nwin = lf_windows(c), wl = lf_window_labels(c), nfb = c->d / NF, nwg = nwin * nfb;
-    const int G = 256;   // instances per pass: the partial sums of one pass are nwin * G * d floats
-    const int rows_max = c->max_b < G ? c->max_b : G;
+    // instances per pass: every pass loads the lists and the weights anew, and its partial sums are nwin * G * d
+    // floats; as many as 4 GiB of partial sums allow, sized once for max_b
+    int G = (int)(((size_t)1 << 32) / ((size_t)nwin * c->d * 4));
+    if (const char* e = getenv("USL_TUNE_BWI_ROWS")) G = atoi(e) < G ? atoi(e) : G;   // tests: several passes on a small layer
+    G = G < 64 ? 64 : G;
+    G = G > c->max_b ? c->max_b : G;
+    const int rows_max = G;
     USL_TRY(usl_reserve(c, (void**)&c->lf_partial, &c->lf_partial_cap, (size_t)nwin * rows_max * c->d * 4));
     const size_t lds = (size_t)WL * 4 + (size_t)NF * 4 + (size_t)NT * 4 + (size_t)NT * 8 + (size_t)NT * 8;
     const unsigned grid = (unsigned)(((nwin + 7) / 8) * 8 * nfb);

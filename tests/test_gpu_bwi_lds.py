@@ -19,7 +19,7 @@ SHAPES = [
     (40000, 32768, 32, 3, "f32"),     # the headline's d and k
     (40000, 32768, 32, 3, "bf16"),
     (66000, 65536, 64, 2, "bf16"),    # d of two histogram chunks
-    (70000, 2048, 2, 300, "f32"),     # two passes over the batch (256 + 44 instances)
+    (70000, 2048, 2, 300, "f32"),     # three passes over the batch (128 + 128 + 44 instances: USL_TUNE_BWI_ROWS below)
     (20, 2048, 2, 1, "f32"),          # fewer labels than LDS banks, most lists empty, one instance
     (131072, 4096, 4, 2, "bf16"),     # exactly four full windows
 ]
@@ -31,8 +31,9 @@ def lds_form(monkeypatch):
 
 
 @pytest.mark.parametrize("m,d,k,b,storage", SHAPES)
-def test_backward_input_register_lists(orc, lds_form, m, d, k, b, storage):
+def test_backward_input_register_lists(orc, lds_form, m, d, k, b, storage, monkeypatch):
     import gpu_util as gu
+    monkeypatch.setenv("USL_TUNE_BWI_ROWS", "128")
     from paper_2306_03725_amd import usl
     cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=200 + SHAPES.index((m, d, k, b, storage)))
     print("bwi lds", m, d, k, b, storage, flush=True)
