@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 2832098918, "forward": 924948889, "backward_weight": 940782387},
-    "large_wide": {"backward_input": 17072390144, "forward": 2478204518, "backward_weight": 2652372992},
+    "large": {"backward_input": 2841116672, "forward": 924948889, "backward_weight": 940782387},
+    "large_wide": {"backward_input": 8576617676, "forward": 2478204518, "backward_weight": 2651219558},
     "stress": {"backward_input": 204285778329, "forward": 26036771225, "backward_weight": 26131772211},
 }
 KERNELS_OF_CALL = {
@@ -34,7 +34,7 @@ KERNELS_OF_CALL = {
     "backward_weight": "k_backward_weight (1 launch)",
     "backward_input": "a look at a sample of g, k_gather_w, then per group of 256 instances k_transpose_g + one "
                       "k_bwd_input_window per window of 24576 labels + k_untile",
-    "backward_input_register_lists": "a look at a sample of g, k_idx_fingerprint, then per group of 256 instances "
+    "backward_input_register_lists": "a look at a sample of g, k_idx_fingerprint, then per pass over the batch "
                                      "k_bwi_lds (lists in registers, rows of g through LDS) + k_lf_reduce",
     "adam": "k_adam (1 launch)",
 }
@@ -55,11 +55,23 @@ def algorithmic_bytes(cfg):
     return per
 
 
+def register_list_windows(cfg, cus=256):
+    """Label windows of usl_backward_input's register-list form for this shape, or 0 where the library keeps the other
+    form (its rule: windows of 16384 to 32768 labels that send about 32 connections into a feature, whole blocks of
+    2048 features, enough workgroups to fill the chip; the windows shortened until the rounds of workgroups are full)."""
+    lists32 = 32 * cfg.d // cfg.k
+    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 16384 <= lists32 <= 32768):
+        return 0
+    cap = min(lists32, 32768) // 4 * 4
+    nwin, nfb = -(-cfg.m // cap), cfg.d // 2048
+    if nwin * nfb * 4 < cus * 3:
+        return 0
+    full = -(-nwin * nfb // cus) * cus // nfb
+    return full if nwin < full <= nwin * 5 // 4 else nwin
+
+
 def register_list_form(cfg):
-    """Whether usl_backward_input takes its register-list form for this shape (the library's rule: about 32
-    connections per window of 32768 labels and feature, whole blocks of 2048 features, enough workgroups)."""
-    return (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 32768 * cfg.k == 32 * cfg.d
-            and -(-cfg.m // 32768) * (cfg.d // 2048) * 4 >= 256 * 3)
+    return register_list_windows(cfg) > 0
 
 
 def launches_in_call(cfg, call):
@@ -67,8 +79,10 @@ def launches_in_call(cfg, call):
     if call != "backward_input":
         return 2 if call == "bce" else 1
     groups = -(-cfg.b // 256)
-    if register_list_form(cfg):
-        return 3 + groups * 2
+    nwin = register_list_windows(cfg)
+    if nwin:
+        passes = -(-cfg.b // max(64, min(cfg.b, (1 << 32) // (nwin * cfg.d * 4))))
+        return 3 + passes * 2
     win = int((24576.0 * ((cfg.d / 32768.0) * (32.0 / cfg.k)) ** 0.5 + 2048.0) / 4096.0) * 4096   # labels per window,
     win = min(max(win, 16384), 49152)                                                              # as the library picks them
     return 3 + groups * (1 + -(-cfg.m // win) + 1 + 1)
