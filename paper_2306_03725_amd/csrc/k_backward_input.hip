@@ -638,7 +638,8 @@ usl_status usl_bwd_input_group(usl_ctx* c, float* grad_x_rows, int32_t rows, uin
 
 usl_status usl_launch_backward_input(usl_ctx* c, const float* g, const int32_t* idx, const void* W,
                                      float* grad_x, int32_t b) {
-    const bool lds_form = usl_bwi_lds_applies(c);
+    // the register-list form copies rows of g and writes grad_x 16 bytes at a time
+    const bool lds_form = usl_bwi_lds_applies(c) && (uintptr_t)g % 16 == 0 && (uintptr_t)grad_x % 16 == 0;
     if (!lds_form) USL_TRY(usl_bwd_input_prepare(c, idx, b));
     // a gradient that is almost all zeros goes through per-instance lists of its nonzeros instead; which of the
     // two paths does the work is decided on the device (gate), both are enqueued

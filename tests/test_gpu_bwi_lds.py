@@ -56,6 +56,29 @@ def test_backward_input_register_lists(orc, lds_form, m, d, k, b, storage, monke
     L.close()
 
 
+def test_buffers_that_are_not_16_byte_aligned(orc, lds_form):
+    """g or grad_x at an address that is not a multiple of 16: the other form does the work."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    m, d, k, b = 70000, 2048, 2, 3
+    cfg = wl.custom(m, d, k, b, positives=3, index=235)
+    idx, W, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_g(cfg)
+    ref = orc.backward_input(g, idx, W, d)
+    L = usl.Layer(m, d, k, b)
+    d_idx, d_W = gu.dev(idx), gu.dev(W)
+    g_store, gx_store = gu.empty((b * m + 1,)), gu.empty((b * d + 1,)).fill_(float("nan"))
+    g_off = g_store[1:].view(b, m)
+    g_off.copy_(torch.from_numpy(g))
+    gx_off = gx_store[1:].view(b, d)
+    assert g_off.data_ptr() % 16 == 4 and gx_off.data_ptr() % 16 == 4
+    gx = gu.empty((b, d))
+    L.backward_input(g_off, d_idx, d_W, gx, b)
+    assert_close(gu.host(gx), ref, 1e-4, "grad_x, g off by 4 bytes")
+    L.backward_input(gu.dev(g), d_idx, d_W, gx_off, b)
+    assert_close(gu.host(gx_off), ref, 1e-4, "grad_x off by 4 bytes")
+    L.close()
+
+
 @pytest.mark.parametrize("pattern", ["two_features", "half_skewed"])
 def test_lists_longer_than_the_registers(orc, lds_form, pattern):
     """Connectivity far from uniform: lists that do not fit a lane's registers go through the overflow list (its
