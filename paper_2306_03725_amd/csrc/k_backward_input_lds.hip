@@ -2,15 +2,15 @@
 //
 //   grad_x[i][c] = sum over connections (j,t) with idx[j][t]==c of W[j][t] * g[i][j]
 //
-// A workgroup owns a window of WL labels and a block of NF features.  Every lane keeps the list of one pair of
+// A workgroup owns a window of wl labels and a block of NF features.  Every lane keeps the list of one pair of
 // features -- (label-in-window, 16 bit) and weight of every connection that leads from the window into the feature
-// -- in registers for the workgroup's whole life, walks the batch staging g[i][window] (WL floats) through LDS with
+// -- in registers for the workgroup's whole life, walks the batch staging g[i][window] (wl floats) through LDS with
 // LDS-DMA, and gathers: the same ds_read_b32 stream as the forward kernel, reading g row-major (no transposed copy
 // of the gradient, no zero flags).  The sums of a window go to partial[window][i][c]; a second kernel adds the
 // windows up.
 //
-// Lists of one (window, feature) have Poisson-distributed lengths (mean WL*k/d = 32 for the shapes this form is
-// used for), registers are allocated for a fixed number of slots.  Per (window, feature block) the features are
+// Lists of one (window, feature) have Poisson-distributed lengths (mean wl*k/d, at most 32: the windows are sized
+// for that), registers are allocated for a fixed number of slots.  Per (window, feature block) the features are
 // therefore ranked by list length and paired longest with shortest: lane l holds list A = rank l from slot 0 upwards
 // and list B = rank NF-1-l from slot KTOT-1 downwards; a wavefront (64 neighbouring ranks: nearly equal lengths)
 // visits slots [0, acap) for its A lists and [KTOT-bcap, KTOT) for its B lists, acap + bcap <= KTOT chosen per
@@ -30,7 +30,7 @@
 namespace {
 
 constexpr int WL = 32768;      // most labels a window has: one float32 row of 128 KiB in LDS.  A layer's windows are of equal
-                               // size wl <= WL (a multiple of 4), as few as WL allows: no short last window whose workgroups idle
+                               // size wl <= WL (a multiple of 4): no short last window whose workgroups idle
 constexpr int NF = 2048;       // features per workgroup (two per lane)
 constexpr int NT = 1024;
 constexpr int KTOT = 68;       // list slots per lane, shared by its two lists (with the rest of the kernel: the 128 registers a lane has)
