@@ -22,6 +22,10 @@ SHAPES = [
     (70000, 2048, 2, 300, "f32"),     # three passes over the batch (128 + 128 + 44 instances: USL_TUNE_BWI_ROWS below)
     (20, 2048, 2, 1, "f32"),          # fewer labels than LDS banks, most lists empty, one instance
     (131072, 4096, 4, 2, "bf16"),     # exactly four full windows
+    (50000, 2048, 8, 3, "f32"),       # k/d = 1/256: windows of 8192 labels at most
+    (30000, 2048, 32, 2, "f32"),      # k/d = 1/64: windows of 2048 labels, the shortest the form takes
+    (99996, 4096, 6, 3, "bf16"),      # a window size that is no power of two (21844 labels at most), k no power of two
+    (65540, 6144, 12, 2, "f32"),      # three feature blocks
 ]
 
 
