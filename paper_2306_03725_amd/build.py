@@ -1,5 +1,6 @@
 """Builds libusl.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
 import os
+import re
 import subprocess
 import sys
 
@@ -23,6 +24,67 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
+def check_untracked_load(verbose=False):
+    """k_bwi_lds warms the L2 with a load issued from inline assembly: the compiler does not know that its result
+    arrives later, so no wait is put behind it -- and nothing but the source's own `s_waitcnt vmcnt(0)` at the top of
+    the next pass protects the destination register.  That holds as long as the compiler neither reads nor writes that
+    register anywhere in the loop (a copy or a spill right behind the load would free it for another value, which the
+    late data would then overwrite).  This looks at the compiler's own assembly listing of the file (same flags as the
+    build) and fails the build if the register is mentioned anywhere in the loop but in the load itself."""
+    src = os.path.join(CSRC, "k_backward_input_lds.hip")
+    lst = os.path.join(HERE, "_build", "k_backward_input_lds.s")
+    subprocess.check_call([_hipcc()] + FLAGS + ["--cuda-device-only", "-S", src, "-o", lst])
+    with open(lst) as fh:
+        checked = scan_listing_for_untracked_load(fh.read().splitlines(), lst)
+    if verbose:
+        print("check_untracked_load: %d warm-up load(s) checked, their registers are untouched inside the loop" % checked, flush=True)
+
+
+def scan_listing_for_untracked_load(lines, lst="listing"):
+    """The check itself, on the lines of an assembly listing; returns the number of loads it looked at."""
+    start = [i for i, l in enumerate(lines) if re.match(r"^_Z\w*k_bwi_lds\w*:", l)]
+    if not start:
+        raise RuntimeError("check_untracked_load: no k_bwi_lds in the listing")
+    checked = 0
+    for f0 in start:
+        f1 = next(i for i in range(f0, len(lines)) if lines[i].startswith(".Lfunc_end"))
+        # basic blocks: (first line, last line, text of the label / comment lines that head the block)
+        heads = [i for i in range(f0, f1) if re.match(r"^(\.LBB\d+_\d+:|; %bb\.\d+:)", lines[i])]
+        blocks = []
+        for n, h in enumerate(heads):
+            end = heads[n + 1] if n + 1 < len(heads) else f1
+            note, j = lines[h], h + 1
+            while j < end and lines[j].lstrip().startswith(";") and "ASM" not in lines[j]:
+                note += " " + lines[j]
+                j += 1
+            blocks.append((h, end, note))
+        loads = [i for i in range(f0, f1) if "ASMSTART" in lines[i - 1] and re.search(r"global_load_dword v\d+, v\d+, s\[", lines[i])]
+        if len(loads) < 1:
+            raise RuntimeError("check_untracked_load: no warm-up load found in %s" % lines[f0])
+        for ld in loads:
+            reg = int(re.search(r"global_load_dword v(\d+),", lines[ld]).group(1))
+            mine = next(b for b in blocks if b[0] <= ld < b[1])
+            m_ = re.search(r"Header=(BB\d+_\d+) Depth=1", mine[2])
+            if not m_:
+                raise RuntimeError("check_untracked_load: the warm-up load is not inside a loop")
+            header = m_.group(1)
+            in_loop = [b for b in blocks if ("Header=%s " % header) in b[2] + " " or ("Parent Loop %s " % header) in b[2] + " "
+                       or lines[b[0]].startswith("." + "L" + header + ":")]
+
+            def mentions(text):
+                if re.search(r"\bv%d\b" % reg, text):
+                    return True
+                return any(int(a) <= reg <= int(b) for a, b in re.findall(r"\bv\[(\d+):(\d+)\]", text))
+            for b0, b1, _ in in_loop:
+                for i in range(b0, b1):
+                    code = lines[i].split(";")[0]
+                    if i != ld and mentions(code):
+                        raise RuntimeError("check_untracked_load: v%d, which receives the warm-up load of k_bwi_lds, is also used at "
+                                           "%s:%d: %s" % (reg, lst, i + 1, lines[i].strip()))
+            checked += 1
+    return checked
+
+
 def build(force=True, verbose=False):
     objs = []
     procs = []
@@ -44,6 +106,9 @@ def build(force=True, verbose=False):
         if p.returncode != 0:
             sys.stderr.write(out)
             raise RuntimeError("hipcc failed on %s" % src)
+    lds_src, lds_lst = os.path.join(CSRC, "k_backward_input_lds.hip"), os.path.join(HERE, "_build", "k_backward_input_lds.s")
+    if force or not os.path.exists(lds_lst) or os.path.getmtime(lds_lst) < max(os.path.getmtime(lds_src), newest_dep):
+        check_untracked_load(verbose)
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     csrc = os.path.join(CSRC, "ceilings.hip")
     if force or not os.path.exists(LIB_CEILINGS) or os.path.getmtime(LIB_CEILINGS) < os.path.getmtime(csrc):

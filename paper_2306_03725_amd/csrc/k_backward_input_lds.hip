@@ -513,7 +513,11 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
             acc = fmaf(n > 1 ? __uint_as_float(o1.y) : 0.f, v1, acc);
         }
     };
-    uint32_t token = 0;   // receives the L2 warm-up loads; reserved until the next vmcnt(0) wait
+    // Receives the L2 warm-up loads, which are issued from inline assembly: the compiler then puts no wait behind them
+    // (behind a load it knows of whose value is never used, or a volatile one, it waits on the spot: a trip to memory
+    // at the start of this wavefront's gathers, 0.14 ms per call at m = 500k).  The register must not be touched until
+    // the vmcnt(0) wait at the top of the next pass; the build checks that in the compiler's listing (build.py).
+    uint32_t token = 0;
     for (int i = 0; i < rows; ++i) {
         const char* grow = reinterpret_cast<const char*>(g + (size_t)w * wl + (size_t)i * m);   // uniform
         {   // the row slice: whole 1 KiB pieces by LDS-DMA, the ragged end through registers

@@ -110,3 +110,38 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(base, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(base, f)
+
+
+def test_build_check_of_the_untracked_warm_up_load():
+    """The build refuses a compile in which the register that receives k_bwi_lds's warm-up load (issued from inline
+    assembly, unknown to the compiler's wait bookkeeping) is touched anywhere else inside the loop."""
+    from paper_2306_03725_amd import build
+    good = """_ZN1_9k_bwi_ldsIfEEvPKf:
+; %bb.0:
+	v_mov_b32_e32 v7, 0
+.LBB0_1:                                ; =>This Loop Header: Depth=1
+	s_waitcnt vmcnt(0)
+	s_barrier
+; %bb.2:                                ;   in Loop: Header=BB0_1 Depth=1
+	;;#ASMSTART
+	global_load_dword v7, v3, s[4:5]
+	;;#ASMEND
+.LBB0_3:                                ;   Parent Loop BB0_1 Depth=1
+                                        ; =>  This Inner Loop Header: Depth=2
+	ds_read_b32 v8, v9
+	s_cbranch_scc1 .LBB0_3
+; %bb.4:                                ;   in Loop: Header=BB0_1 Depth=1
+	s_cbranch_scc1 .LBB0_1
+; %bb.5:
+	v_mov_b32_e32 v7, 0
+	s_endpgm
+.Lfunc_end0:
+""".splitlines()
+    assert build.scan_listing_for_untracked_load(good) == 1
+    for bad_line, where in (("\tv_mov_b32_e32 v12, v7", "ds_read_b32 v8, v9"), ("\tscratch_store_dwordx2 off, v[6:7], off", "s_barrier")):
+        bad = list(good)
+        bad.insert(next(i for i, l in enumerate(bad) if where in l), bad_line)
+        with pytest.raises(RuntimeError, match="v7"):
+            build.scan_listing_for_untracked_load(bad)
+    with pytest.raises(RuntimeError, match="no warm-up load"):
+        build.scan_listing_for_untracked_load([l for l in good if "global_load_dword" not in l])
