@@ -35,6 +35,14 @@ constexpr int NF = 2048;       // features per workgroup (two per lane)
 constexpr int NT = 1024;
 constexpr int KTOT = 68;       // list slots per lane, shared by its two lists (with the rest of the kernel: the 128 registers a lane has)
 constexpr uint32_t PAD_SLOT = 0xFFFFFFFFu;
+// LDS of the gather kernel: the row slice, NF floats through which the sums are un-permuted, NT words (the features of
+// every lane), NT entries of 8 bytes (the nearest part of the overflow list), 2 * NT words (each lane's share of it) and
+// 32 words of zeros, one per bank: what the empty places of a list read (weight 0 times a real gradient would turn an
+// infinity in g into NaNs in features that have nothing to do with it).  ZERO_LABEL + b is the "label" whose address is
+// zero word b; it fits the 16 bits of a packed label.
+constexpr size_t LDS_BYTES = (size_t)32768 * 4 + (size_t)2048 * 4 + (size_t)1024 * 4 + (size_t)1024 * 8 + (size_t)1024 * 8 + 128;
+constexpr uint32_t ZERO_LABEL = (uint32_t)((LDS_BYTES - 128) / 4);
+static_assert(ZERO_LABEL % 32 == 0 && ZERO_LABEL + 31 < 65536 && LDS_BYTES <= 160 * 1024, "zero words: bank b, 16-bit label, inside LDS");
 constexpr int CHUNK = 32768;   // features per LDS histogram
 
 __global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
@@ -150,6 +158,7 @@ k_lf_plan(const uint32_t* __restrict__ count, int d, int nfb, uint32_t* __restri
         const uint32_t cw = cap_of[lane_of[q] >> 6];
         const uint32_t cap = zone_of[q] == 0 ? (cw & 0xFFu) : (cw >> 8);
         ov[q] = n[q] > cap ? n[q] - cap : 0u;
+        ov[q] = (ov[q] + 1u) & ~1u;   // an even number of places: the list's lane walks them two at a time
     }
     auto block_scan = [&](uint32_t mine) -> uint32_t {   // inclusive, over the lanes of the workgroup
         __syncthreads();
@@ -245,7 +254,7 @@ k_lf_fill(const int32_t* __restrict__ idx, int64_t m, int k, int d, int wl, int 
 // free, then lanes whose banks are all taken double up on the least loaded one --, the same construction as for the
 // slots of a label in the forward product, with one addition: a list shorter than the wavefront's allowance has
 // empty places, which may go to any step and read any bank.  A lane that finds no bank among its entries spends an
-// empty place (reading a label whose bank is free: with a zero weight) while it has one.
+// empty place (it then reads the zero word of a free bank, see ZERO_LABEL) while it has one.
 // One half-wavefront per (workgroup of the gather kernel, zone, 32 lanes); lane i is list i and also bank i.
 // Reads the lists as k_lf_fill grouped them (ent), writes them ordered into the places the gather kernel loads its
 // registers from (lab / slot: [workgroup][slot][lane]) and what exceeds the allowance into the overflow list.  Any
@@ -254,7 +263,7 @@ constexpr int SG = 8;   // half-wavefronts per workgroup
 __global__ void __launch_bounds__(SG * 32)
 k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent_base, const uint32_t* __restrict__ where,
               const uint32_t* __restrict__ count, const uint16_t* __restrict__ feat, const uint32_t* __restrict__ caps,
-              const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, int64_t m, int k, int d, int wl, int nfb,
+              const uint32_t* __restrict__ ov_base, const uint32_t* __restrict__ ov_off, int k, int d, int wl, int nfb,
               int rounds, uint16_t* __restrict__ lab, uint32_t* __restrict__ slot, OvEntry* __restrict__ ov) {
     __shared__ uint8_t slots[SG][32][KTOT + 4];   // my entries sorted by bank
     __shared__ uint8_t left_in[SG][32][36];       // entries of mine not placed yet, per bank
@@ -269,7 +278,6 @@ k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent
     const uint32_t cw = caps[wg * (NT / 64) + (half >> 1)];
     const int cap = zone ? (int)(cw >> 8) : (int)(cw & 0xFFu);
     const int w = (int)(wg / nfb), fb = (int)(wg % nfb);
-    const bool wide = m - (int64_t)w * wl >= 32;   // the window has a label for every bank
     auto at = [&](int p) -> size_t { return (wg * KTOT + (zone ? KTOT - 1 - p : p)) * NT + half * 32 + lane; };
     // my list: feature, length, where its entries are; label of an entry = its flat slot / k, counted from the window's first
     const uint32_t f = feat[(wg * 2 + zone) * NT + half * 32 + lane];
@@ -283,9 +291,14 @@ k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent
         o.feature = (uint16_t)f; o.label = (uint16_t)label_of(my[p]); o.slot = my[p];
         ov[(size_t)ov_base[wg] + ov_off[bin] + (p - (uint32_t)cap)] = o;
     }
+    if (len > (uint32_t)cap && ((len - (uint32_t)cap) & 1u)) {   // an odd number: one empty place behind them
+        OvEntry o;
+        o.feature = (uint16_t)f; o.label = (uint16_t)ZERO_LABEL; o.slot = PAD_SLOT;
+        ov[(size_t)ov_base[wg] + ov_off[bin] + (len - (uint32_t)cap)] = o;
+    }
     if (rounds <= 0) {
         for (int s = 0; s < cap; ++s) {
-            lab[at(s)] = s < n ? (uint16_t)label_of(my[s]) : (uint16_t)0;
+            lab[at(s)] = s < n ? (uint16_t)label_of(my[s]) : (uint16_t)ZERO_LABEL;
             slot[at(s)] = s < n ? my[s] : PAD_SLOT;
         }
         return;   // the whole wavefront: rounds is the same for all
@@ -396,8 +409,8 @@ k_lf_schedule(const uint32_t* __restrict__ ent, const uint32_t* __restrict__ ent
                 if (lane == bb) ++myload;
             }
         }
-        if (wb >= 0) {             // an empty place: a label of the free bank, no weight
-            lab[at(s)] = (uint16_t)(wide ? wb : 0);
+        if (wb >= 0) {             // an empty place: the zero word of the free bank, no weight
+            lab[at(s)] = (uint16_t)(ZERO_LABEL + (uint32_t)wb);
             slot[at(s)] = PAD_SLOT;
         } else {                   // my next unplaced entry in that bank
             const int pick = mine[ends[mb] - cnt[mb]];
@@ -442,9 +455,7 @@ __device__ __forceinline__ void gather4(float& acc, uint32_t p0, uint32_t p1, fl
 
 // The gathers.  grid: ceil(nwin / 8) * 8 * nfb workgroups; all feature blocks of a window run on one XCD (workgroups
 // are dealt to the 8 XCDs round robin), so its slice of g is fetched from HBM once and served from that XCD's L2.
-// LDS: [0, WL*4) the row slice, then NF floats through which the sums are un-permuted, then NT words: the features
-// of every lane, then NT entries of 8 bytes: the nearest part of the overflow list, then
-// 2 * NT words: each lane's share of it.
+// LDS: see LDS_BYTES.
 template <typename TS>
 __global__ void __launch_bounds__(NT)
 k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int k, int rows, int d, int wl, int nfb, int nwin,
@@ -490,27 +501,29 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
     uint2* ov_near = reinterpret_cast<uint2*>(feat_of + NT);
     if (threadIdx.x < ov_n) {
         const OvEntry o = ov[(size_t)ov0 + threadIdx.x];
-        ov_near[threadIdx.x] = make_uint2((uint32_t)o.label * 4u, __float_as_uint(usl_load_f32<TS>(W, (size_t)o.slot)));
+        ov_near[threadIdx.x] = make_uint2((uint32_t)o.label * 4u,   // an empty place: the zero word, no weight
+                                          o.slot == PAD_SLOT ? 0u : __float_as_uint(usl_load_f32<TS>(W, (size_t)o.slot)));
     } else {
-        ov_near[threadIdx.x] = make_uint2(0u, 0u);
+        ov_near[threadIdx.x] = make_uint2(ZERO_LABEL * 4u, 0u);
     }
     // ... and which of them belong to the lane's two lists (start | n << 16)
     uint32_t* ovr_a = reinterpret_cast<uint32_t*>(ov_near + NT);
     uint32_t* ovr_b = ovr_a + NT;
     ovr_a[threadIdx.x] = ovr[(wg * 2 + 0) * NT + threadIdx.x];
     ovr_b[threadIdx.x] = ovr[(wg * 2 + 1) * NT + threadIdx.x];
+    if (threadIdx.x < 32) reinterpret_cast<uint32_t*>(lds_raw)[ZERO_LABEL + threadIdx.x] = 0u;
     const int nl = (int)min((int64_t)wl, m - (int64_t)w * wl);   // labels of this window (the last one may be short)
     const int nv = nl / 4, full = nv & ~63;                      // 16-byte pieces of a row slice; those in whole 1 KiB runs
     const int lines = (nl * 4 + 127) / 128, per = (lines + nfb - 1) / nfb;   // 128-byte lines; this workgroup's share of the warm-up
     const bool warms = (int)threadIdx.x < per && fb * per + (int)threadIdx.x < lines;
-    // the rest of a list (r = start | n << 16 in ov_near), two entries in flight at a time
+    // the rest of a list (r = start | n << 16 in ov_near, n even), two entries in flight at a time
     auto more = [&](float& acc, uint32_t r) {
-        for (uint32_t q = r & 0xFFFFu, n = r >> 16; n; q += 2, n = n > 2 ? n - 2 : 0) {
-            const uint2 o0 = ov_near[q], o1 = ov_near[min(q + 1, (uint32_t)NT - 1)];
+        for (uint32_t q = r & 0xFFFFu, e = q + (r >> 16); q < e; q += 2) {
+            const uint2 o0 = ov_near[q], o1 = ov_near[q + 1];
             const float v0 = *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(o0.x));
             const float v1 = *reinterpret_cast<lds_f32_t*>(static_cast<uintptr_t>(o1.x));
             acc = fmaf(__uint_as_float(o0.y), v0, acc);
-            acc = fmaf(n > 1 ? __uint_as_float(o1.y) : 0.f, v1, acc);
+            acc = fmaf(__uint_as_float(o1.y), v1, acc);
         }
     };
     // Receives the L2 warm-up loads, which are issued from inline assembly: the compiler then puts no wait behind them
@@ -562,7 +575,7 @@ k_bwi_lds(const float* __restrict__ g, const TS* __restrict__ W, int64_t m, int 
             __syncthreads();
             for (uint32_t q = NT + threadIdx.x; q < ov_n; q += NT) {
                 const OvEntry o = ov[(size_t)ov0 + q];
-                unsafeAtomicAdd(&outbuf[o.feature], usl_load_f32<TS>(W, (size_t)o.slot) * row[o.label]);
+                if (o.slot != PAD_SLOT) unsafeAtomicAdd(&outbuf[o.feature], usl_load_f32<TS>(W, (size_t)o.slot) * row[o.label]);
             }
         }
         __syncthreads();
@@ -652,7 +665,7 @@ static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     USL_TRY(usl_reserve(c, (void**)&c->lf_slot, &c->lf_slot_cap, (size_t)nwg * KTOT * NT * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_ent, &c->lf_ent_cap, N * 4));
     USL_TRY(usl_reserve(c, (void**)&c->lf_ovoff, &c->lf_ovoff_cap, nbins * 4));
-    USL_TRY(usl_reserve(c, (void**)&c->lf_ov, &c->lf_ov_cap, N * sizeof(OvEntry)));
+    USL_TRY(usl_reserve(c, (void**)&c->lf_ov, &c->lf_ov_cap, (N + nbins) * sizeof(OvEntry)));   // worst case, + an empty place per list
     int rounds = 3;                // of proposals per step of the bank-aware order; 0 = lists stay as filled
     if (const char* e = getenv("USL_TUNE_ROUNDS")) rounds = atoi(e);
     uint32_t* ov_base = c->lf_ov_base;               // [nwg + 1]
@@ -677,7 +690,7 @@ static usl_status lf_build(usl_ctx* c, const int32_t* idx) {
     hipLaunchKernelGGL(k_lf_fill, grid, dim3(NT), lds, c->stream, idx, c->m, c->k, c->d, wl, nfb, splits, c->lf_where, c->lf_taken,
                        ent_base, c->lf_ent);
     hipLaunchKernelGGL(k_lf_schedule, dim3((unsigned)(nwg * 64 / SG)), dim3(SG * 32), 0, c->stream, c->lf_ent, ent_base,
-                       c->lf_where, c->lf_count, c->lf_feat, c->lf_caps, ov_base, c->lf_ovoff, c->m, c->k, c->d, wl, nfb, rounds,
+                       c->lf_where, c->lf_count, c->lf_feat, c->lf_caps, ov_base, c->lf_ovoff, c->k, c->d, wl, nfb, rounds,
                        c->lf_lab, c->lf_slot, reinterpret_cast<OvEntry*>(c->lf_ov));
     USL_TRY(usl_idx_fingerprint(c, idx, 1));
     USL_TRY(usl_check_launch(c, "register lists of the input gradient"));
@@ -703,7 +716,7 @@ usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const
     G = G > c->max_b ? c->max_b : G;
     const int rows_max = G;
     USL_TRY(usl_reserve(c, (void**)&c->lf_partial, &c->lf_partial_cap, (size_t)nwin * rows_max * c->d * 4));
-    const size_t lds = (size_t)WL * 4 + (size_t)NF * 4 + (size_t)NT * 4 + (size_t)NT * 8 + (size_t)NT * 8;
+    const size_t lds = LDS_BYTES;
     const unsigned grid = (unsigned)(((nwin + 7) / 8) * 8 * nfb);
     const uint32_t* ov_base = c->lf_ov_base;
     (void)nwg;

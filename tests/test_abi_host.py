@@ -143,5 +143,10 @@ def test_build_check_of_the_untracked_warm_up_load():
         bad.insert(next(i for i, l in enumerate(bad) if where in l), bad_line)
         with pytest.raises(RuntimeError, match="v7"):
             build.scan_listing_for_untracked_load(bad)
+    spilled = list(good)
+    at = next(i for i, l in enumerate(spilled) if "ds_read_b32 v8, v9" in l)
+    spilled[at:at] = ["\tscratch_load_dword v20, off, off", "\tscratch_load_dword v21, off, off offset:4"]
+    with pytest.raises(RuntimeError, match="register reloads"):
+        build.scan_listing_for_untracked_load(spilled)
     with pytest.raises(RuntimeError, match="no warm-up load"):
         build.scan_listing_for_untracked_load([l for l in good if "global_load_dword" not in l])

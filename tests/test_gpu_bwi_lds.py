@@ -60,6 +60,38 @@ def test_backward_input_register_lists(orc, lds_form, m, d, k, b, storage, monke
     L.close()
 
 
+@pytest.mark.parametrize("pattern", ["uniform", "two_features"])
+def test_an_infinite_gradient_stays_in_its_own_features(orc, lds_form, pattern):
+    """One entry of g is +inf: exactly the features its label is connected to become infinite (or NaN where a weight
+    is zero or another infinity cancels), every other feature is finite and right.  The empty places of the register
+    lists and of the overflow lists must not multiply it by their zero weight."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    m, d, k, b = 40000, 2048, 2, 2
+    cfg = wl.custom(m, d, k, b, positives=3, index=236)
+    idx, W, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_g(cfg)
+    if pattern == "two_features":
+        idx[:, 0], idx[:, 1] = 7, 2040
+    j_inf = 0      # label 0 is what an empty place would read if it read a real label
+    g[1, j_inf] = np.inf
+    W[j_inf, :] = np.abs(W[j_inf, :]) + 0.5
+    L = usl.Layer(m, d, k, b)
+    gx = gu.empty((b, d)).fill_(float("nan"))
+    L.backward_input(gu.dev(g), gu.dev(idx), gu.dev(W), gx, b)
+    got = gu.host(gx)
+    g_fin = g.copy()
+    g_fin[1, j_inf] = 0.0
+    ref = orc.backward_input(g_fin, idx, W, d)
+    touched = np.zeros(d, bool)
+    touched[idx[j_inf]] = True
+    assert np.isposinf(got[1, touched]).all()
+    assert np.isfinite(got[1, ~touched]).all() and np.isfinite(got[0]).all()
+    rest = got.copy()
+    rest[1, touched] = ref[1, touched]
+    assert_close(rest, ref, 1e-4, "grad_x away from the infinite entry")
+    L.close()
+
+
 def test_buffers_that_are_not_16_byte_aligned(orc, lds_form):
     """g or grad_x at an address that is not a multiple of 16: the other form does the work."""
     import gpu_util as gu
