@@ -25,7 +25,7 @@ def _hipcc():
 
 
 def check_untracked_load(verbose=False):
-    """k_bwi_lds warms the L2 with a load issued from inline assembly: the compiler does not know that its result
+    """k_bwi_lds and k_both_lds warm the L2 with a load issued from inline assembly: the compiler does not know that its result
     arrives later, so no wait is put behind it -- and nothing but the source's own `s_waitcnt vmcnt(0)` at the top of
     the next pass protects the destination register.  That holds as long as the compiler neither reads nor writes that
     register anywhere in the loop (a copy or a spill right behind the load would free it for another value, which the
@@ -35,14 +35,19 @@ def check_untracked_load(verbose=False):
     lst = os.path.join(HERE, "_build", "k_backward_input_lds.s")
     subprocess.check_call([_hipcc()] + FLAGS + ["--cuda-device-only", "-S", src, "-o", lst])
     with open(lst) as fh:
-        checked = scan_listing_for_untracked_load(fh.read().splitlines(), lst)
+        text = fh.read().splitlines()
+    try:
+        checked = scan_listing_for_untracked_load(text, lst)
+    except RuntimeError:
+        os.rename(lst, lst + ".failed")   # so that an incremental build checks again
+        raise
     if verbose:
         print("check_untracked_load: %d warm-up load(s) checked, their registers are untouched inside the loop" % checked, flush=True)
 
 
 def scan_listing_for_untracked_load(lines, lst="listing"):
     """The check itself, on the lines of an assembly listing; returns the number of loads it looked at."""
-    start = [i for i, l in enumerate(lines) if re.match(r"^_Z\w*k_bwi_lds\w*:", l)]
+    start = [i for i, l in enumerate(lines) if re.match(r"^_Z\w*k_(bwi|both)_lds\w*:", l)]
     if not start:
         raise RuntimeError("check_untracked_load: no k_bwi_lds in the listing")
     checked = 0
@@ -58,18 +63,26 @@ def scan_listing_for_untracked_load(lines, lst="listing"):
                 note += " " + lines[j]
                 j += 1
             blocks.append((h, end, note))
-        loads = [i for i in range(f0, f1) if "ASMSTART" in lines[i - 1] and re.search(r"global_load_dword v\d+, v\d+, s\[", lines[i])]
+        loads = [i for i in range(f0, f1) if "ASMSTART" in lines[i - 1] and re.search(r"global_load_dword v\d+, (v\d+, s\[|v\[\d+:\d+\], off)", lines[i])]
         if len(loads) < 1:
             raise RuntimeError("check_untracked_load: no warm-up load found in %s" % lines[f0])
         for ld in loads:
             reg = int(re.search(r"global_load_dword v(\d+),", lines[ld]).group(1))
             mine = next(b for b in blocks if b[0] <= ld < b[1])
-            m_ = re.search(r"Header=(BB\d+_\d+) Depth=1", mine[2])
+            m_ = re.search(r"Header=(BB\d+_\d+) Depth=(\d+)", mine[2])
             if not m_:
                 raise RuntimeError("check_untracked_load: the warm-up load is not inside a loop")
             header = m_.group(1)
-            in_loop = [b for b in blocks if ("Header=%s " % header) in b[2] + " " or ("Parent Loop %s " % header) in b[2] + " "
-                       or lines[b[0]].startswith("." + "L" + header + ":")]
+            if m_.group(2) != "1":   # in a loop inside the loop over the passes: the outermost one is meant
+                inner = next(b for b in blocks if lines[b[0]].startswith("." + "L" + header + ":"))
+                m_ = re.search(r"Parent Loop (BB\d+_\d+) Depth=1", inner[2])
+                if not m_:
+                    raise RuntimeError("check_untracked_load: no outermost loop found around the warm-up load")
+                header = m_.group(1)
+            # the loop's blocks: from its header to the last block that names it (loops are laid out in one piece)
+            first = next(b[0] for b in blocks if lines[b[0]].startswith("." + "L" + header + ":"))
+            last = max(b[1] for b in blocks if ("Header=%s " % header) in b[2] + " " or ("Parent Loop %s " % header) in b[2] + " ")
+            in_loop = [b for b in blocks if first <= b[0] < last]
 
             def mentions(text):
                 if re.search(r"\bv%d\b" % reg, text):

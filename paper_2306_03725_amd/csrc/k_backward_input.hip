@@ -534,7 +534,7 @@ usl_status build_csc(usl_ctx* c, const int32_t* idx) {
     USL_TRY(usl_idx_fingerprint(c, idx, 1));
     USL_TRY(usl_check_launch(c, "column lists"));
     c->csc_built_for = idx;
-    c->lf_built_for = nullptr;   // one fingerprint: it belongs to the lists built last
+    c->lf[0].built_for = c->lf[1].built_for = nullptr;   // one fingerprint: it belongs to the lists built last
     return USL_OK;
 }
 

@@ -269,6 +269,59 @@ k_adam(TS* __restrict__ W, const float* __restrict__ gW, float* __restrict__ m1,
     }
 }
 
+// The same update where the weight gradient arrives in the order of the register lists of the input-gradient kernel
+// (k_both_lds: stage[pos[f]] is slot f's gradient): picked up here, written to grad_W in passing (whole lines), so
+// that the kernel that computed it does not scatter it (4 bytes per line there).  A block works on the f of one
+// eighth of the array, the eighth of its XCD (blocks are dealt to the 8 XCDs round robin): the part of stage that
+// the slots of a window point into (a few MiB) is then fetched by one L2 only and stays there while they are done.
+// gate (may be null): zero means the kernels over the listed nonzero gradients wrote grad_W themselves; read it.
+template <typename TS>
+__global__ void __launch_bounds__(256)
+k_adam_staged(TS* __restrict__ W, const float* __restrict__ stage, const uint32_t* __restrict__ pos,
+              const uint32_t* __restrict__ gate, float* __restrict__ gW, float* __restrict__ m1, float* __restrict__ m2,
+              size_t n4, float lr, float b1, float b2, float eps, float ic1, float ic2) {
+    const bool listed = gate && *gate == 0;
+    const size_t per_xcd = (n4 + 7) / 8, first = (size_t)(blockIdx.x & 7) * per_xcd;
+    const size_t last = first + per_xcd < n4 ? first + per_xcd : n4;
+    const size_t stride = (size_t)(gridDim.x / 8) * 256;
+    for (size_t v = first + (size_t)(blockIdx.x >> 3) * 256 + threadIdx.x; v < last; v += stride) {
+        const size_t f = v * 4;
+        float4 g4;
+        if (listed) {
+            g4 = *reinterpret_cast<const float4*>(gW + f);
+        } else {
+            const uint4 p4 = *reinterpret_cast<const uint4*>(pos + f);
+            g4 = make_float4(stage[p4.x], stage[p4.y], stage[p4.z], stage[p4.w]);
+            *reinterpret_cast<float4*>(gW + f) = g4;
+        }
+        float4 a4 = *reinterpret_cast<const float4*>(m1 + f);
+        float4 v4 = *reinterpret_cast<const float4*>(m2 + f);
+        float w[4];
+        if (sizeof(TS) == 4) {
+            const float4 w4 = *reinterpret_cast<const float4*>(W + f);
+            w[0] = w4.x; w[1] = w4.y; w[2] = w4.z; w[3] = w4.w;
+        } else {
+            const uint2 u = *reinterpret_cast<const uint2*>(W + f);
+            w[0] = __uint_as_float(u.x << 16); w[1] = __uint_as_float(u.x & 0xFFFF0000u);
+            w[2] = __uint_as_float(u.y << 16); w[3] = __uint_as_float(u.y & 0xFFFF0000u);
+        }
+        w[0] = adam_one(w[0], g4.x, a4.x, v4.x, lr, b1, b2, eps, ic1, ic2);
+        w[1] = adam_one(w[1], g4.y, a4.y, v4.y, lr, b1, b2, eps, ic1, ic2);
+        w[2] = adam_one(w[2], g4.z, a4.z, v4.z, lr, b1, b2, eps, ic1, ic2);
+        w[3] = adam_one(w[3], g4.w, a4.w, v4.w, lr, b1, b2, eps, ic1, ic2);
+        *reinterpret_cast<float4*>(m1 + f) = a4;
+        *reinterpret_cast<float4*>(m2 + f) = v4;
+        if (sizeof(TS) == 4) {
+            *reinterpret_cast<float4*>(W + f) = make_float4(w[0], w[1], w[2], w[3]);
+        } else {
+            uint2 u;
+            u.x = (uint32_t)usl_f32_to_bf16(w[0]) | ((uint32_t)usl_f32_to_bf16(w[1]) << 16);
+            u.y = (uint32_t)usl_f32_to_bf16(w[2]) | ((uint32_t)usl_f32_to_bf16(w[3]) << 16);
+            *reinterpret_cast<uint2*>(W + f) = u;
+        }
+    }
+}
+
 }  // namespace
 
 // Per-block loss sums of either loss kernel, sized once for max_b instances: a later, larger batch never
@@ -379,6 +432,25 @@ usl_status usl_launch_adam(usl_ctx* c, void* W, const float* grad_W, float* m1, 
         hipLaunchKernelGGL(k_adam<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
                            (uint16_t*)W, grad_W, m1, m2, n, lr, beta1, beta2, eps, inv_c1, inv_c2);
     return usl_check_launch(c, "adam");
+}
+
+// Adam from a weight gradient in list order (see k_adam_staged); m * k must be a multiple of 4 (the list form's
+// shapes are).  grad_W is written (or, behind a zero gate, read).
+usl_status usl_launch_adam_staged(usl_ctx* c, void* W, const float* stage, const uint32_t* pos, const uint32_t* gate,
+                                  float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
+                                  float inv_c1, float inv_c2) {
+    const size_t n = (size_t)c->m * c->k;
+    const bool aligned = ((uintptr_t)W % 16 == 0) && ((uintptr_t)grad_W % 16 == 0) &&
+                         ((uintptr_t)m1 % 16 == 0) && ((uintptr_t)m2 % 16 == 0);
+    if (!aligned || n % 4) USL_FAIL(c, USL_EINVAL, "W, grad_W, m1, m2 must be 16-byte aligned, m * k a multiple of 4");
+    const unsigned blocks = (unsigned)(c->num_cu > 0 ? c->num_cu : 8) * 16 / 8 * 8;
+    if (c->storage == USL_F32)
+        hipLaunchKernelGGL(k_adam_staged<float>, dim3(blocks), dim3(256), 0, c->stream, (float*)W, stage, pos, gate,
+                           grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
+    else
+        hipLaunchKernelGGL(k_adam_staged<uint16_t>, dim3(blocks), dim3(256), 0, c->stream, (uint16_t*)W, stage, pos, gate,
+                           grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
+    return usl_check_launch(c, "adam (staged gradient)");
 }
 
 // ---- rows of idx / W picked by a list of label ids (label-subset calls) ----------------------

@@ -33,12 +33,16 @@ extern "C" usl_status usl_destroy(usl_ctx* c) {
         void* bufs[] = {c->bce_partials, c->sel_hist, c->prune_flags, c->tie_counts, c->counter64,
                         c->csc_ptr, c->csc_cursor, c->csc_order, c->csc_slot, c->csc_w, c->gT, c->gxT, c->nz_flags,
                         c->slot_order, c->topk_cand, c->sub_idx, c->sub_W, c->predict_out, c->gw_part,
-                        c->nz_state, c->nz_lab, c->nz_val, c->idx_print,
-                        c->lf_count, c->lf_taken, c->lf_where, c->lf_feat, c->lf_caps, c->lf_ov_base, c->lf_ovr, c->lf_lab, c->lf_ent, c->lf_ovoff,
-                        c->lf_slot, c->lf_ov, c->lf_partial};
+                        c->nz_state, c->nz_lab, c->nz_val, c->idx_print};
         (void)hipStreamSynchronize(c->stream);
         for (void* p : bufs)
             if (p) (void)hipFree(p);
+        for (auto& L : c->lf) {
+            void* lists[] = {L.count, L.taken, L.where, L.feat, L.caps, L.ov_base, L.ovr, L.lab, L.slot, L.ent, L.ovoff,
+                             L.ov, L.stage, L.pos, L.partial};
+            for (void* p : lists)
+                if (p) (void)hipFree(p);
+        }
         if (c->hint_host) (void)hipHostFree(c->hint_host);
     }
     free(c);
@@ -56,7 +60,7 @@ extern "C" const char* usl_last_error(const usl_ctx* c) { return c ? c->err : "n
 extern "C" usl_status usl_invalidate(usl_ctx* c) {
     if (!c) return USL_EINVAL;
     c->csc_built_for = nullptr;
-    c->lf_built_for = nullptr;
+    c->lf[0].built_for = c->lf[1].built_for = nullptr;
     c->slot_order_for = nullptr;
     return USL_OK;
 }
@@ -117,7 +121,7 @@ extern "C" usl_status usl_init_indices(usl_ctx* c, int32_t* idx, uint64_t seed) 
     NEED(idx);
     USL_TRY(usl_prepare_device(c));
     c->csc_built_for = nullptr;
-    c->lf_built_for = nullptr;
+    c->lf[0].built_for = c->lf[1].built_for = nullptr;
     c->slot_order_for = nullptr;
     return usl_launch_init_indices(c, idx, seed);
 }
@@ -258,7 +262,7 @@ static usl_status subset_context(usl_ctx* c, int64_t n, const int32_t* idx, cons
     usl_status s = usl_prepare_device(sub);
     if (s != USL_OK) USL_FAIL(c, s, "%s", sub->err);
     sub->csc_built_for = nullptr;
-    sub->lf_built_for = nullptr;    // same scratch pointer, new contents
+    sub->lf[0].built_for = sub->lf[1].built_for = nullptr;    // same scratch pointer, new contents
     sub->slot_order_for = nullptr;
     const size_t esize = c->storage == USL_F32 ? 4 : 2;
     USL_TRY(usl_reserve(c, (void**)&c->sub_idx, &c->sub_idx_cap, (size_t)n * c->k * 4));
@@ -349,7 +353,7 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
         // that, its nonzeros are listed once and both backward products try the lists first (k_sparse_grad.hip).
         const int G = usl_bwd_input_group_rows();
         const bool lists = loss_kind == 1 && usl_sparse_supported(c);
-        if (usl_bwi_lds_applies(c) || (lists && (b > G || usl_sparse_expected(c)))) {
+        if (usl_bwi_lds_applies(c) || usl_both_lds_applies(c) || (lists && (b > G || usl_sparse_expected(c)))) {
             // squared hinge where a gradient of almost only zeros is expected (or the batch has several groups, and
             // the look at the gradient needs all of it): the loss writes the gradient row-major only, its nonzeros are
             // listed once, and both backward products use the lists (the dense kernels stand by behind the gate)
@@ -359,10 +363,28 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
             if (lists) USL_TRY(usl_sparse_compact(c, g, b, &gate));
             c->nz_lists_of = g;
             c->nz_lists_tried = gate != nullptr;
-            usl_status s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);
-            if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
+            usl_status s;
+            const float* stage = nullptr;
+            const uint32_t* pos = nullptr;
+            if (usl_both_lds_applies(c) && (uintptr_t)g % 16 == 0 && (uintptr_t)grad_x % 16 == 0 && (uintptr_t)x % 16 == 0) {
+                // both products from one pass of gathers over the rows of g (k_backward_input_lds.hip); behind the
+                // gate like the two dense kernels it stands for
+                s = USL_OK;
+                if (gate) s = usl_sparse_backward_weight(c, x, idx, grad_W, b);
+                if (gate && s == USL_OK) s = usl_sparse_backward_input(c, idx, W, grad_x, b);
+                if (s == USL_OK) s = usl_both_lds_run(c, g, x, idx, W, grad_x, b, gate, &stage, &pos);
+            } else {
+                s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);
+                if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
+            }
             c->nz_lists_of = nullptr;
             USL_TRY(s);
+            if (stage) {   // the weight gradient is in the order of the lists: Adam picks it up there and writes grad_W
+                const double c1 = 1.0 - pow((double)beta1, (double)t);
+                const double c2 = 1.0 - pow((double)beta2, (double)t);
+                return usl_launch_adam_staged(c, W, stage, pos, gate, grad_W, m1, m2, lr, beta1, beta2, eps, (float)(1.0 / c1),
+                                              (float)(1.0 / c2));
+            }
         } else {
             USL_TRY(usl_bwd_input_prepare(c, idx, b));
             const uint32_t* gate = nullptr;
@@ -409,7 +431,7 @@ extern "C" usl_status usl_redistribute(usl_ctx* c, int32_t* idx, void* W, float*
     if (n == 0) return USL_OK;
     USL_TRY(usl_prepare_device(c));
     c->csc_built_for = nullptr;
-    c->lf_built_for = nullptr;
+    c->lf[0].built_for = c->lf[1].built_for = nullptr;
     c->slot_order_for = nullptr;
     return usl_launch_redistribute(c, idx, W, m1, m2, n, seed, epoch);
 }
@@ -423,7 +445,7 @@ extern "C" usl_status usl_redistribute_rows(usl_ctx* c, int32_t* idx, void* W, f
     if (per_row == 0) return USL_OK;
     USL_TRY(usl_prepare_device(c));
     c->csc_built_for = nullptr;
-    c->lf_built_for = nullptr;
+    c->lf[0].built_for = c->lf[1].built_for = nullptr;
     c->slot_order_for = nullptr;
     return usl_launch_redistribute_rows(c, idx, W, m1, m2, per_row, seed, epoch);
 }
@@ -438,7 +460,7 @@ extern "C" usl_status usl_check(usl_ctx* c) {
         if (stale) {
             USL_HIP(c, hipMemset(reinterpret_cast<uint32_t*>(c->idx_print) + 4, 0, 4));
             c->csc_built_for = nullptr;
-            c->lf_built_for = nullptr;
+            c->lf[0].built_for = c->lf[1].built_for = nullptr;
             c->slot_order_for = nullptr;
             USL_FAIL(c, USL_ESTALE, "idx changed without usl_invalidate: a usl_backward_input call since the last "
                                     "check ran on column lists of the old contents and filled grad_x with NaN");

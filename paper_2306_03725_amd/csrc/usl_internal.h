@@ -59,22 +59,27 @@ struct usl_ctx {
     uint32_t* hint_dev;       // the same words as the device addresses them
     uint32_t hint_seen, probe_serial;
     int sparse_streak;        // looks in a row that found the sample sparse
-    // the input gradient's feature-stationary form (k_backward_input_lds.hip): per (label window, feature block)
-    // workgroup the register lists of its lanes, their plan, what did not fit, and the windows' partial sums
-    uint32_t* lf_count;       size_t lf_count_cap;    // [nwin*d] list lengths
-    uint32_t* lf_taken;       size_t lf_taken_cap;    // [nwin*d] positions handed out while filling
-    uint32_t* lf_where;       size_t lf_where_cap;    // [nwin*d] where a feature's list starts among its workgroup's entries
-    uint16_t* lf_feat;        size_t lf_feat_cap;     // [wg][2][1024] feature of a lane's list
-    uint32_t* lf_caps;        size_t lf_caps_cap;     // [wg][16] slots the wavefronts visit
-    uint32_t* lf_ov_base;     size_t lf_ov_base_cap;  // [wg+1] start of a workgroup's overflow entries, [wg] their number; the same two for all its entries
-    uint32_t* lf_ovr;         size_t lf_ovr_cap;      // [wg][2][1024] a lane's lists' share of the overflow entries held in LDS
-    uint16_t* lf_lab;         size_t lf_lab_cap;      // [wg][slots][1024] label within the window
-    uint32_t* lf_slot;        size_t lf_slot_cap;     // [wg][slots][1024] flat slot j*k+t (where the weight lives)
-    uint32_t* lf_ent;         size_t lf_ent_cap;      // [m*k] flat slots grouped by (workgroup, feature), before the bank-aware order
-    uint32_t* lf_ovoff;       size_t lf_ovoff_cap;    // [nwin*d] where a list's overflow starts in its workgroup's
-    void* lf_ov;              size_t lf_ov_cap;       // overflow entries
-    float* lf_partial;        size_t lf_partial_cap;  // [nwin][rows of a pass][d]
-    const int32_t* lf_built_for;                      // idx pointer the lists were built from (NULL = stale)
+    // the register-list form of the input gradient (k_backward_input_lds.hip): [0] lists of 68 slots per lane from
+    // windows of up to 32768 labels, for usl_backward_input; [1] lists of 36 slots from windows of half that length, for
+    // the kernel of usl_train_step that computes the weight gradient from the same gathers
+    struct usl_lf {
+        uint32_t* count;      size_t count_cap;    // [nwin*d] list lengths
+        uint32_t* taken;      size_t taken_cap;    // [nwin*d] positions handed out while filling
+        uint32_t* where;      size_t where_cap;    // [nwin*d] where a feature's list starts among its workgroup's entries
+        uint16_t* feat;       size_t feat_cap;     // [wg][2][1024] feature of a lane's list
+        uint32_t* caps;       size_t caps_cap;     // [wg][16] slots the wavefronts visit
+        uint32_t* ov_base;    size_t ov_base_cap;  // [wg+1] start of a workgroup's overflow entries, [wg] their number; the same two for all its entries
+        uint32_t* ovr;        size_t ovr_cap;      // [wg][2][1024] a lane's lists' share of the overflow entries held in LDS
+        uint16_t* lab;        size_t lab_cap;      // [wg][slots][1024] label within the window
+        uint32_t* slot;       size_t slot_cap;     // [wg][slots][1024] flat slot j*k+t (where the weight lives)
+        uint32_t* ent;        size_t ent_cap;      // [m*k] flat slots grouped by (workgroup, feature), before the bank-aware order
+        uint32_t* ovoff;      size_t ovoff_cap;    // [nwin*d] where a list's overflow starts in its workgroup's
+        void* ov;             size_t ov_cap;       // overflow entries
+        float* stage;         size_t stage_cap;    // [1] only: the weight gradient in list order, [wg][slots][1024], then one per overflow entry
+        uint32_t* pos;        size_t pos_cap;      // [1] only: [m*k] where a slot's weight gradient is in stage
+        float* partial;       size_t partial_cap;  // [nwin][rows of a pass][d]
+        const int32_t* built_for;                  // idx pointer the lists were built from (NULL = stale)
+    } lf[2];
 };
 
 #define USL_FAIL(ctx, code, ...)                                   \
@@ -133,6 +138,14 @@ usl_status usl_bwd_input_group(usl_ctx* ctx, float* grad_x_rows, int32_t rows, u
 bool usl_bwi_lds_applies(const usl_ctx* ctx);
 usl_status usl_bwi_lds_run(usl_ctx* ctx, const float* g, const int32_t* idx, const void* W, float* grad_x, int32_t b,
                            const uint32_t* gate);
+// Both backward products from one pass of gathers through register lists of half the length (k_backward_input_lds.hip):
+// grad_W[m][k] and grad_x[b][d] from g[b][m] and x[b][d]; for layers with k / d <= 1/1024, one pass over the batch.
+bool usl_both_lds_applies(const usl_ctx* ctx);
+usl_status usl_both_lds_run(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx, const void* W, float* grad_x,
+                            int32_t b, const uint32_t* gate, const float** stage, const uint32_t** pos);
+usl_status usl_launch_adam_staged(usl_ctx* ctx, void* W, const float* stage, const uint32_t* pos, const uint32_t* gate,
+                                  float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
+                                  float inv_c1, float inv_c2);
 // Records (store = 1) the fingerprint of idx in ctx->idx_print, or compares with the recorded one (store = 0) and
 // raises the stale word (32-bit word 4 of idx_print) on a difference.
 usl_status usl_idx_fingerprint(usl_ctx* ctx, const int32_t* idx, int store);

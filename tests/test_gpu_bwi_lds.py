@@ -164,18 +164,22 @@ def test_changed_idx_is_noticed(orc, lds_form):
 
 # the last three: a layer large enough for the kernels of the large layers (float32, k = 32, one row of x per stage);
 # targets with an empty instance, a label listed twice and a dense instance
+# both = "on": the kernel that computes the weight gradient from the same gathers (lists of half the length)
+@pytest.mark.parametrize("both", ["off", "on"])
 @pytest.mark.parametrize("loss_kind,storage,easy,shape", [
     (0, "f32", False, (70000, 2048, 2, 9)), (1, "bf16", False, (70000, 2048, 2, 9)), (1, "f32", True, (70000, 2048, 2, 9)),
-    (0, "f32", False, (270000, 32768, 32, 5)), (1, "f32", False, (270000, 32768, 32, 5)), (1, "f32", True, (270000, 32768, 32, 5))])
-def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy, shape, monkeypatch):
+    (0, "f32", False, (270000, 32768, 32, 5)), (1, "f32", False, (270000, 32768, 32, 5)), (1, "f32", True, (270000, 32768, 32, 5)),
+    (0, "bf16", False, (100000, 8192, 8, 37)), (0, "f32", False, (20, 2048, 2, 1))])
+def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy, shape, both, monkeypatch):
     """The fused step where the input gradient takes this form: loss row-major, then the products."""
     import gpu_util as gu
     from paper_2306_03725_amd import usl
     if easy:
         monkeypatch.setenv("USL_TUNE_SPARSE", "always")
+    monkeypatch.setenv("USL_TUNE_BOTH", both)
     m, d, k, b = shape
-    cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=250 + loss_kind)
-    print("train_step lds", shape, loss_kind, storage, easy, flush=True)
+    cfg = wl.custom(m, d, k, b, storage=storage, positives=min(3, m), index=250 + loss_kind)
+    print("train_step lds", shape, loss_kind, storage, easy, both, flush=True)
     hp = wl.ADAM
     idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
     if easy:
@@ -210,4 +214,33 @@ def test_train_step_with_register_lists(orc, lds_form, loss_kind, storage, easy,
     assert_close(gu.host(d_m1), m1r, 1e-4, "m1")
     assert_close(gu.host(d_m2), m2r, 1e-4, "m2")
     L.check()
+    L.close()
+
+
+@pytest.mark.parametrize("pattern", ["two_features", "half_skewed"])
+def test_both_products_with_lists_longer_than_the_registers(orc, lds_form, pattern, monkeypatch):
+    """The step whose backward products share one pass of gathers, on connectivity far from uniform: the weight
+    gradients of overflow entries are summed in LDS and, beyond what LDS holds, in memory."""
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    monkeypatch.setenv("USL_TUNE_BOTH", "on")
+    m, d, k, b = 40000, 2048, 2, 3
+    cfg = wl.custom(m, d, k, b, positives=3, index=260)
+    hp = wl.ADAM
+    idx, W, x = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg)
+    if pattern == "two_features":
+        idx[:, 0], idx[:, 1] = 7, 2040
+    else:
+        idx[::2, 0] = (np.arange(0, m, 2) % 5) * 400 + 3
+        idx[::2, 1] = (np.arange(0, m, 2) % 5) * 400 + 4
+    off, lab = wl.gen_targets(cfg)
+    m1, m2 = np.zeros((m, k), np.float32), np.zeros((m, k), np.float32)
+    scale = float(np.float32(1.0 / b))
+    L = usl.Layer(m, d, k, b)
+    g, gW, gx, loss = gu.empty((b, m)), gu.empty((m, k)).fill_(float("nan")), gu.empty((b, d)).fill_(float("nan")), gu.empty((1,))
+    L.train_step(gu.dev(x), gu.dev(idx), gu.dev(W), gu.dev(m1), gu.dev(m2), gu.dev(off), gu.dev(lab), 0, scale, 1,
+                 hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], g, gW, gx, loss, b)
+    got_g = gu.host(g)
+    assert_close(gu.host(gW), orc.backward_weight(got_g, x, idx), 1e-5, "grad_W")
+    assert_close(gu.host(gx), orc.backward_input(got_g, idx, W, d), 1e-4, "grad_x")
     L.close()
