@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the uniformly-sparse output layer's train step on one MI355X.
 
-One step = forward + sparse-target BCE (loss and gradient) + backward-weight + backward-input +
-Adam, plus a connection redistribution after every `period`-th step, on seeded synthetic data
+One step = forward + sparse-target BCE (loss and gradient) + the two backward products (weight and input
+gradient) + Adam, plus a connection redistribution after every `period`-th step, on seeded synthetic data
 of the headline workload (m=500,000 labels, d=32,768, fan-in k=32, batch 256, float32).
 All inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
 """
@@ -24,9 +24,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward_input": 2841116672, "forward": 924948889, "backward_weight": 940782387},
-    "large_wide": {"backward_input": 8576617676, "forward": 2478204518, "backward_weight": 2651219558},
-    "stress": {"backward_input": 204285778329, "forward": 26036771225, "backward_weight": 26131772211},
+    "large": {"backward": 3905316454, "backward_input": 2843423539, "forward": 924948889, "backward_weight": 940782387},
+    "large_wide": {"backward": 11245348454, "backward_input": 8593290035, "forward": 2478309376, "backward_weight": 2652058419},
+    "stress": {"backward": 230453621555, "backward_input": 204321744486, "forward": 26036561510, "backward_weight": 26131877068},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
@@ -36,6 +36,10 @@ KERNELS_OF_CALL = {
                       "k_bwd_input_window per window of 24576 labels + k_untile",
     "backward_input_register_lists": "a look at a sample of g, k_idx_fingerprint, then per pass over the batch "
                                      "k_bwi_lds (lists in registers, rows of g through LDS) + k_lf_reduce",
+    "backward": "usl_backward_weight's and usl_backward_input's kernels, one call after the other",
+    "backward_one_pass": "a look at a sample of g, k_idx_fingerprint, k_both_lds (both products from one pass over g: "
+                         "lists in registers with a weight-gradient sum per connection, two rows of g through LDS at a "
+                         "time) + k_lf_reduce + k_unstage (the weight gradient into slot order)",
     "adam": "k_adam (1 launch)",
 }
 
@@ -52,6 +56,10 @@ def algorithmic_bytes(cfg):
         "adam": (es + 12) * N + (es + 8) * N,
     }
     per["step"] = sum(per.values())
+    # usl_backward is scored against the bytes of the two separate calls it stands for; read once, g, idx and the
+    # list of connections would be 4E + (8 + es)N + (es + 4)X
+    per["backward"] = per["backward_weight"] + per["backward_input"]
+    per["backward_one_pass_lower_bound"] = 4 * E + (8 + es) * N + (es + 4) * X
     return per
 
 
@@ -74,8 +82,29 @@ def register_list_form(cfg):
     return register_list_windows(cfg) > 0
 
 
+def one_pass_windows(cfg, cus=256):
+    """Label windows of usl_backward's one-pass form (both products from one pass over g), or 0 where the library runs
+    the two separate products (its rule: windows of 15968 labels at most that send about 16 connections into a
+    feature, 16 * d / k >= 16384, whole blocks of 2048 features, enough workgroups to fill the chip, the partial sums
+    of the whole batch within 4 GiB)."""
+    lists16 = 16 * cfg.d // cfg.k
+    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and lists16 == 16384):
+        return 0
+    cap = min(lists16, 15968) // 4 * 4
+    nwin, nfb = -(-cfg.m // cap), cfg.d // 2048
+    full = -(-nwin * nfb // cus) * cus // nfb
+    nwin = full if nwin < full <= nwin * 5 // 4 else nwin
+    if nwin * nfb * 4 < cus * 3 or nwin * cfg.b * cfg.d * 4 > 1 << 32:
+        return 0
+    return nwin
+
+
 def launches_in_call(cfg, call):
     """Kernel launches behind one call (the HIP-event time of the call covers all of them)."""
+    if call == "backward":
+        if one_pass_windows(cfg):
+            return 3 + 3
+        return launches_in_call(cfg, "backward_weight") + launches_in_call(cfg, "backward_input")
     if call != "backward_input":
         return 2 if call == "bce" else 1
     groups = -(-cfg.b // 256)
@@ -155,7 +184,7 @@ class Bench:
         return False
 
     def step(self, ev=None):
-        """The step as five separate calls, with an event between the calls when ev is a list."""
+        """The step as four separate calls, with an event between the calls when ev is a list."""
         hp, b, L = self.wl.ADAM, self.cfg.b, self.L
         self.t += 1
         x = self.xs[self.t % len(self.xs)]
@@ -170,8 +199,7 @@ class Bench:
         mark()
         L.forward(x, self.idx, self.W, self.out, b); mark()
         L.bce_loss_grad(self.out, off, lab, self.scale, self.out, self.loss, b); mark()
-        L.backward_weight(self.out, x, self.idx, self.gW, b); mark()
-        L.backward_input(self.out, self.idx, self.W, self.gx, b); mark()
+        L.backward(self.out, x, self.idx, self.W, self.gW, self.gx, b); mark()
         L.adam_step(self.W, self.gW, self.m1, self.m2, self.t, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"]); mark()
         if self._redistribute():
             mark()
@@ -205,11 +233,14 @@ class Bench:
         self.torch.cuda.empty_cache()
 
 
-CALLS = ["forward", "bce", "backward_weight", "backward_input", "adam", "redistribute"]
+CALLS = ["forward", "bce", "backward", "adam", "redistribute"]        # the step as separate calls
+STAGES = ["forward", "bce", "backward", "adam"]                       # ... those that every step has
+ALONE = ["backward_weight", "backward_input"]                         # the two products of usl_backward, each by its own call
 
 
 def per_call_breakdown(B, steps):
-    """The same steps as separate calls with an event between the calls: ms per call and per step."""
+    """The same steps as separate calls with an event between the calls: ms per call and per step; then each of the two
+    backward products by its own entry point, on the gradient the last step left."""
     events = []
     B.step()
     sep = B.timed(lambda: B.step(events), steps)
@@ -217,7 +248,13 @@ def per_call_breakdown(B, steps):
     for marks in events:
         for i in range(len(marks) - 1):
             per_call[CALLS[i]].append(marks[i].elapsed_time(marks[i + 1]))
-    return {c: (float(np.mean(v)) if v else None) for c, v in per_call.items()}, sep
+    res = {c: (float(np.mean(v)) if v else None) for c, v in per_call.items()}
+    x, b, n = B.xs[0], B.cfg.b, max(2, min(steps, 10))
+    for name, fn in (("backward_weight", lambda: B.L.backward_weight(B.out, x, B.idx, B.gW, b)),
+                     ("backward_input", lambda: B.L.backward_input(B.out, B.idx, B.W, B.gx, b))):
+        fn()
+        res[name] = B.timed(fn, n)
+    return res, sep
 
 
 def workload_summary(name, steps, warmup, torch, usl, wl):
@@ -238,9 +275,9 @@ def workload_summary(name, steps, warmup, torch, usl, wl):
            "hbm_frac_of_peak": round(ab["step"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
            "separate_calls_ms_per_step": round(sep, 4),
            "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
-           "call_frac_of_peak": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) for c in CALLS[:5]},
+           "call_frac_of_peak": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) for c in STAGES + ALONE},
            "bad_rows": B.L.validate_indices(B.idx), "redistributions": B.epoch}
-    dom = max(CALLS[:5], key=lambda c: call_ms[c] or 0.0)
+    dom = max(STAGES, key=lambda c: call_ms[c] or 0.0)
     res["roofline"] = {"bound": "hbm", "kernel": "usl_" + dom, "ms_per_launch": round(call_ms[dom], 4),
                        "launches_in_call": launches_in_call(cfg, dom), "algorithmic_bytes": ab[dom],
                        "achieved": round(ab[dom] / (call_ms[dom] * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -266,7 +303,7 @@ def main():
                     help="also time the squared-hinge loss and the two backward calls on gradients with "
                          "0 / 90 / 99 / 99.9 %% exact zeros (implicit negative mining, Section 3.3)")
     ap.add_argument("--separate-calls", action="store_true",
-                    help="time the step as five separate calls instead of usl_train_step")
+                    help="time the step as four separate calls instead of usl_train_step")
     ap.add_argument("--predict", action="store_true",
                     help="also time prediction (Section 2): top-5 labels of every score row and the P@k hit counts")
     ap.add_argument("--ceilings", action="store_true",
@@ -320,20 +357,23 @@ def main():
     ab = algorithmic_bytes(cfg)
     steps_per_s = 1e3 / ms_per_step
     # the dominant call and its roofline position (algorithmic bytes / measured time)
-    dom = max((c for c in calls[:5]), key=lambda c: call_ms[c] or 0.0)
+    dom = max(STAGES, key=lambda c: call_ms[c] or 0.0)
     dom_gbps = ab[dom] / (call_ms[dom] * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom)
     if args.traffic_kib is not None:
         traffic = args.traffic_kib * 1024
-    dom_kernels = KERNELS_OF_CALL["backward_input_register_lists" if dom == "backward_input" and register_list_form(cfg) else dom]
+    dom_kernels = KERNELS_OF_CALL["backward_one_pass" if dom == "backward" and one_pass_windows(cfg) else dom]
     roof = {"bound": "hbm", "kernel": "usl_%s: %s" % (dom, dom_kernels),
             "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBPS, 4),
             "ms_per_launch": round(call_ms[dom], 4), "launches_in_call": launches_in_call(cfg, dom),
             "algorithmic_bytes": ab[dom],
             "traffic": traffic,
-            "note": "dominant call of the step (usl_train_step runs the same kernels); achieved = algorithmic bytes "
-                    "of the call / HIP-event time of the call on the launch stream, which covers launches_in_call "
+            "one_pass_lower_bound_bytes": ab["backward_one_pass_lower_bound"] if dom == "backward" else None,
+            "note": "dominant call of the step (usl_train_step runs the same kernels, except that Adam takes the weight "
+                    "gradient from where k_both_lds left it and k_unstage is not needed); achieved = algorithmic bytes "
+                    "of the call (for usl_backward: of the two separate products it stands for) / HIP-event time of "
+                    "the call on the launch stream, which covers launches_in_call "
                     "kernel launches (per-kernel durations: profiles/train_step_*_kernel_trace.txt); traffic = HBM "
                     "bytes per call from rocprofv3 counters (profiles/train_step_*_hbm_bytes.txt), measured offline"}
     step_gbps = ab["step"] / (ms_per_step * 1e-3) / 1e9
@@ -348,10 +388,10 @@ def main():
         "achieved_hbm_GBps": round(step_gbps, 1), "hbm_frac_of_peak": round(step_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_GB_per_step": round(ab["step"] / 1e9, 4),
         "call_ms": {c: (round(v, 4) if v is not None else None) for c, v in call_ms.items()},
-        "call_GBps": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9, 1) for c in calls[:5]},
+        "call_GBps": {c: round(ab[c] / (call_ms[c] * 1e-3) / 1e9, 1) for c in STAGES + ALONE},
         "wall_ms_per_step": round(wall_ms / args.steps, 4),
-        "timed_path": ("separate calls: usl_forward, usl_bce_loss_grad, usl_backward_weight, usl_backward_input, "
-                       "usl_adam_step" if args.separate_calls else "usl_train_step (the same five stages in one call)")
+        "timed_path": ("separate calls: usl_forward, usl_bce_loss_grad, usl_backward, usl_adam_step"
+                       if args.separate_calls else "usl_train_step (the same stages in one call)")
                       + ", usl_redistribute on its schedule",
         "separate_calls_ms_per_step": round(separate_ms, 4),
         "loss": loss_value, "bad_rows": n_bad, "redistributions": B.epoch,
@@ -362,22 +402,25 @@ def main():
             from paper_2306_03725_amd import ceilings
             c = ceilings.run()
             cu, ghz = c["compute_units"], c["clock_GHz"]
-            gathers = 3.0 * b * m * k                       # one LDS gather per (instance, connection) and product
+            # one LDS gather per (instance, connection) and product; the two backward products share theirs where
+            # usl_backward takes its one-pass form
+            products = 2.0 if one_pass_windows(cfg) else 3.0
+            gathers = products * b * m * k
             gather_rate = c["lds_gather_b32_conflict_free_lanes_per_clk_cu"] * cu * ghz * 1e9
             es = 2 if cfg.storage == "bf16" else 4
             # every product stages its rows into the LDS of every workgroup: per product, label (or feature)
             # blocks of 2048 x batch rows x row bytes
-            copy_bytes = 3.0 * (-(-m // 2048)) * b * d * es
+            copy_bytes = products * (-(-m // 2048)) * b * d * es
             t_gather = gathers / gather_rate * 1e3
             t_copy = copy_bytes / (c["l2_to_lds_row_copy_aggregate_GBps"] * 1e9) * 1e3
             t_hbm = ab["step"] / (c["hbm_copy_GBps_read_plus_write"] * 1e9) * 1e3
             res["ceilings"] = {k_: round(v, 3) for k_, v in c.items()}
             roof["gather_frac"] = round(t_gather / ms_per_step, 4)
-            roof["gather_note"] = ("3*b*m*k LDS gathers per step at the measured conflict-free ds_read_b32 rate "
+            roof["gather_note"] = ("%d*b*m*k LDS gathers per step at the measured conflict-free ds_read_b32 rate "
                                    "would take %.3f ms; staging the rows those gathers read, at the measured L2 to "
                                    "LDS copy rate, %.3f ms; the step's algorithmic HBM bytes at the measured copy "
                                    "rate, %.3f ms; these three do not overlap inside a product kernel"
-                                   % (t_gather, t_copy, t_hbm))
+                                   % (int(products), t_gather, t_copy, t_hbm))
             roof["measured_ceilings_frac"] = round((t_gather + t_copy + t_hbm) / ms_per_step, 4)
         except Exception as exc:   # the headline line must survive a failure of an appended leg
             res["ceilings"] = {"error": repr(exc)}

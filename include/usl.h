@@ -157,6 +157,15 @@ usl_status usl_backward_weight(usl_ctx* ctx, const float* g, const void* x, cons
 usl_status usl_backward_input(usl_ctx* ctx, const float* g, const int32_t* idx, const void* W,
                               float* grad_x, int32_t b);
 
+/* Both gradients of the backward pass in one call (Section 3.3, Algorithms 2 and 3): grad_W as usl_backward_weight
+ * leaves it, grad_x as usl_backward_input does, from the same g [b][m], x [b][d], idx [m][k], W [m][k]; all device
+ * pointers, grad_W [m][k] and grad_x [b][d] float32, both overwritten, neither may alias an input.  Where the shape
+ * allows, every gathered g[i][j] serves both products (one pass over g instead of two); elsewhere the call is the
+ * two separate ones.  Errors as for those: USL_EINVAL for a null pointer or b outside [1, max_b], USL_EHIP if a
+ * launch fails.  The order of the additions is not fixed. */
+usl_status usl_backward(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx, const void* W,
+                        float* grad_W, float* grad_x, int32_t b);
+
 /* The three products restricted to a list of labels (Section 6, outlook: with the uniform format, scoring a
  * subset of labels, e.g. sampled negatives, is a slicing of the [m][k] arrays).  rows[n_rows]: int32
  * label ids in [0, m), device memory, any order, repeats allowed (each occurrence is its own row):

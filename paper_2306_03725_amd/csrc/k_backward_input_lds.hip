@@ -957,7 +957,9 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
     }
 }
 
-// grad_x[i][c] = sum over the windows of partial[w][i][c]
+// grad_x[i][c] = sum over the windows of partial[w][i][c].  BOTH only names the kernel after the one whose sums it
+// adds (twice the windows there), so that a profile tells the two apart.
+template <bool BOTH>
 __global__ void __launch_bounds__(256)
 k_lf_reduce(const float4* __restrict__ partial, int nwin, size_t n4, float4* __restrict__ out,
             const uint32_t* __restrict__ gate, const uint32_t* __restrict__ stale) {
@@ -1172,7 +1174,7 @@ static usl_status lf_run_t(usl_ctx* c, int set, const float* g, const void* x, c
         }
 #undef USL_LDS_FORM
         const size_t n4 = (size_t)rows * c->d / 4;
-        hipLaunchKernelGGL(k_lf_reduce, dim3(c->num_cu * 8), dim3(256), 0, c->stream,
+        hipLaunchKernelGGL(k_lf_reduce<BOTH>, dim3(c->num_cu * 8), dim3(256), 0, c->stream,
                            reinterpret_cast<const float4*>(L.partial), nwin, n4,
                            reinterpret_cast<float4*>(grad_x + (size_t)i0 * c->d), gate, stale);
     }

@@ -269,6 +269,21 @@ k_adam(TS* __restrict__ W, const float* __restrict__ gW, float* __restrict__ m1,
     }
 }
 
+// grad_W[f] = stage[pos[f]]: the weight gradient of k_both_lds brought into the order of the slots (for callers of
+// usl_backward; usl_train_step lets Adam do it in passing).  Blocks and XCDs as in k_adam_staged.
+__global__ void __launch_bounds__(256)
+k_unstage(const float* __restrict__ stage, const uint32_t* __restrict__ pos, const uint32_t* __restrict__ gate,
+          float* __restrict__ gW, size_t n4) {
+    if (gate && *gate == 0) return;
+    const size_t per_xcd = (n4 + 7) / 8, first = (size_t)(blockIdx.x & 7) * per_xcd;
+    const size_t last = first + per_xcd < n4 ? first + per_xcd : n4;
+    const size_t stride = (size_t)(gridDim.x / 8) * 256;
+    for (size_t v = first + (size_t)(blockIdx.x >> 3) * 256 + threadIdx.x; v < last; v += stride) {
+        const uint4 p4 = reinterpret_cast<const uint4*>(pos)[v];
+        reinterpret_cast<float4*>(gW)[v] = make_float4(stage[p4.x], stage[p4.y], stage[p4.z], stage[p4.w]);
+    }
+}
+
 // The same update where the weight gradient arrives in the order of the register lists of the input-gradient kernel
 // (k_both_lds: stage[pos[f]] is slot f's gradient): picked up here, written to grad_W in passing (whole lines), so
 // that the kernel that computed it does not scatter it (4 bytes per line there).  A block works on the f of one
@@ -432,6 +447,14 @@ usl_status usl_launch_adam(usl_ctx* c, void* W, const float* grad_W, float* m1, 
         hipLaunchKernelGGL(k_adam<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, c->stream,
                            (uint16_t*)W, grad_W, m1, m2, n, lr, beta1, beta2, eps, inv_c1, inv_c2);
     return usl_check_launch(c, "adam");
+}
+
+usl_status usl_launch_unstage(usl_ctx* c, const float* stage, const uint32_t* pos, const uint32_t* gate, float* grad_W) {
+    const size_t n = (size_t)c->m * c->k;
+    if ((uintptr_t)grad_W % 16 || n % 4) USL_FAIL(c, USL_EINVAL, "grad_W must be 16-byte aligned, m * k a multiple of 4");
+    const unsigned blocks = (unsigned)(c->num_cu > 0 ? c->num_cu : 8) * 16 / 8 * 8;
+    hipLaunchKernelGGL(k_unstage, dim3(blocks), dim3(256), 0, c->stream, stage, pos, gate, grad_W, n / 4);
+    return usl_check_launch(c, "weight gradient into slot order");
 }
 
 // Adam from a weight gradient in list order (see k_adam_staged); m * k must be a multiple of 4 (the list form's

@@ -278,6 +278,47 @@ static usl_status subset_context(usl_ctx* c, int64_t n, const int32_t* idx, cons
         if (s_ != USL_OK) USL_FAIL(c, s_, "%s", sub->err);        \
     } while (0)
 
+// Both backward products of one g.  The nonzeros of g are listed once where the context expects few (as in
+// usl_train_step); the kernels over the lists and the dense ones stand on either side of the gate.
+static usl_status backward_both(usl_ctx* c, const float* g, const void* x, const int32_t* idx, const void* W, float* grad_W,
+                                float* grad_x, int32_t b, bool lists, bool dense, const uint32_t** gate_out,
+                                const float** stage, const uint32_t** pos) {
+    const uint32_t* gate = nullptr;
+    if (lists) USL_TRY(usl_sparse_compact(c, g, b, &gate));
+    c->nz_lists_of = g;
+    c->nz_lists_tried = gate != nullptr;
+    usl_status s = USL_OK;
+    *stage = nullptr;
+    *pos = nullptr;
+    if (usl_both_lds_applies(c) && (uintptr_t)g % 16 == 0 && (uintptr_t)grad_x % 16 == 0 && (uintptr_t)x % 16 == 0) {
+        // both products from one pass of gathers over the rows of g (k_backward_input_lds.hip); behind the gate like
+        // the two dense kernels it stands for.  The weight gradient is left in the order of the lists.
+        if (gate) s = usl_sparse_backward_weight(c, x, idx, grad_W, b);
+        if (gate && s == USL_OK) s = usl_sparse_backward_input(c, idx, W, grad_x, b);
+        if (s == USL_OK) s = usl_both_lds_run(c, g, x, idx, W, grad_x, b, gate, stage, pos);
+    } else {
+        s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, dense);
+        if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
+    }
+    c->nz_lists_of = nullptr;
+    *gate_out = gate;
+    return s;
+}
+
+extern "C" usl_status usl_backward(usl_ctx* c, const float* g, const void* x, const int32_t* idx, const void* W,
+                                   float* grad_W, float* grad_x, int32_t b) {
+    if (!c) return USL_EINVAL;
+    NEED(g); NEED(x); NEED(idx); NEED(W); NEED(grad_W); NEED(grad_x);
+    USL_TRY(check_batch(c, b));
+    USL_TRY(usl_prepare_device(c));
+    const uint32_t* gate = nullptr;
+    const float* stage = nullptr;
+    const uint32_t* pos = nullptr;
+    USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, usl_sparse_supported(c), false, &gate, &stage, &pos));
+    if (stage) USL_TRY(usl_launch_unstage(c, stage, pos, gate, grad_W));
+    return USL_OK;
+}
+
 extern "C" usl_status usl_forward_rows(usl_ctx* c, const void* x, const int32_t* idx, const void* W,
                                        const int32_t* rows, int64_t n_rows, float* out_rows, int32_t b) {
     if (!c) return USL_EINVAL;
@@ -360,25 +401,9 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
             USL_TRY(usl_launch_loss(c, loss_kind, g, tgt_off, tgt_lab, scale, g, loss, b));
             // (the same order of calls where the input gradient reads g row-major: its register-list form)
             const uint32_t* gate = nullptr;
-            if (lists) USL_TRY(usl_sparse_compact(c, g, b, &gate));
-            c->nz_lists_of = g;
-            c->nz_lists_tried = gate != nullptr;
-            usl_status s;
             const float* stage = nullptr;
             const uint32_t* pos = nullptr;
-            if (usl_both_lds_applies(c) && (uintptr_t)g % 16 == 0 && (uintptr_t)grad_x % 16 == 0 && (uintptr_t)x % 16 == 0) {
-                // both products from one pass of gathers over the rows of g (k_backward_input_lds.hip); behind the
-                // gate like the two dense kernels it stands for
-                s = USL_OK;
-                if (gate) s = usl_sparse_backward_weight(c, x, idx, grad_W, b);
-                if (gate && s == USL_OK) s = usl_sparse_backward_input(c, idx, W, grad_x, b);
-                if (s == USL_OK) s = usl_both_lds_run(c, g, x, idx, W, grad_x, b, gate, &stage, &pos);
-            } else {
-                s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, loss_kind == 0);
-                if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
-            }
-            c->nz_lists_of = nullptr;
-            USL_TRY(s);
+            USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, lists, loss_kind == 0, &gate, &stage, &pos));
             if (stage) {   // the weight gradient is in the order of the lists: Adam picks it up there and writes grad_W
                 const double c1 = 1.0 - pow((double)beta1, (double)t);
                 const double c2 = 1.0 - pow((double)beta2, (double)t);

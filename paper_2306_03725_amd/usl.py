@@ -20,7 +20,7 @@ SYMBOLS = ["usl_bce_loss_grad_noalloc", "usl_check", "usl_create", "usl_destroy"
            "usl_version", "usl_init_indices", "usl_forward", "usl_bce_loss_grad", "usl_sqh_loss_grad",
            "usl_topk", "usl_precision_hits", "usl_train_step", "usl_redistribute_rows", "usl_predict",
            "usl_forward_rows", "usl_backward_weight_rows", "usl_backward_input_rows",
-           "usl_backward_weight", "usl_backward_input", "usl_adam_step", "usl_redistribute",
+           "usl_backward_weight", "usl_backward_input", "usl_backward", "usl_adam_step", "usl_redistribute",
            "usl_validate_indices", "usl_philox_words"]
 
 if not os.path.exists(LIB_PATH):
@@ -52,6 +52,7 @@ _sig = {
     "usl_precision_hits": [_vp, _vp, _vp, _vp, _i32, _i32, _vp],
     "usl_backward_weight": [_vp, _vp, _vp, _vp, _vp, _i32],
     "usl_backward_input": [_vp, _vp, _vp, _vp, _vp, _i32],
+    "usl_backward": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32],
     "usl_adam_step": [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32],
     "usl_redistribute": [_vp, _vp, _vp, _vp, _vp, _f64, _u64, _u64, ctypes.POINTER(_i64)],
     "usl_redistribute_rows": [_vp, _vp, _vp, _vp, _vp, _i32, _u64, _u64],
@@ -184,6 +185,10 @@ class Layer:
     def backward_input(self, g, idx, W, grad_x, b):
         self._same_idx(idx)
         self._ck(_lib.usl_backward_input(self._h, _ptr(g), _ptr(idx), _ptr(W), _ptr(grad_x), b))
+
+    def backward(self, g, x, idx, W, grad_W, grad_x, b):
+        self._same_idx(idx)
+        self._ck(_lib.usl_backward(self._h, _ptr(g), _ptr(x), _ptr(idx), _ptr(W), _ptr(grad_W), _ptr(grad_x), b))
 
     def adam_step(self, W, grad_W, m1, m2, t, lr, beta1, beta2, eps):
         self._ck(_lib.usl_adam_step(self._h, _ptr(W), _ptr(grad_W), _ptr(m1), _ptr(m2), t, lr,

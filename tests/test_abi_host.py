@@ -150,3 +150,34 @@ def test_build_check_of_the_untracked_warm_up_load():
         build.scan_listing_for_untracked_load(spilled)
     with pytest.raises(RuntimeError, match="no warm-up load"):
         build.scan_listing_for_untracked_load([l for l in good if "global_load_dword" not in l])
+    # the kernel for both products issues its warm-up loads from a loop over lines, inside the loop over the passes
+    # (full addresses, no scalar base): the loop over the passes is the one that is searched
+    nested = """_ZN1_10k_both_ldsIfEEvPKf:
+; %bb.0:
+	v_mov_b32_e32 v5, 0
+.LBB1_1:                                ; =>This Loop Header: Depth=1
+                                        ;     Child Loop BB1_3 Depth 2
+	s_waitcnt vmcnt(0)
+	s_barrier
+; %bb.2:                                ;   in Loop: Header=BB1_1 Depth=1
+	v_mov_b32_e32 v6, v0
+.LBB1_3:                                ;   Parent Loop BB1_1 Depth=1
+                                        ; =>  This Inner Loop Header: Depth=2
+	v_cmp_le_i32_e32 vcc, s71, v6
+; %bb.4:                                ;   in Loop: Header=BB1_3 Depth=2
+	;;#ASMSTART
+	global_load_dword v5, v[12:13], off
+	;;#ASMEND
+	s_cbranch_execnz .LBB1_3
+; %bb.5:                                ;   in Loop: Header=BB1_1 Depth=1
+	ds_read_b32 v8, v9
+	s_cbranch_scc1 .LBB1_1
+; %bb.6:
+	s_endpgm
+.Lfunc_end1:
+""".splitlines()
+    assert build.scan_listing_for_untracked_load(nested) == 1
+    bad = list(nested)
+    bad.insert(next(i for i, l in enumerate(bad) if "ds_read_b32 v8, v9" in l), "\tv_add_u32_e32 v5, v5, v9")
+    with pytest.raises(RuntimeError, match="v5"):
+        build.scan_listing_for_untracked_load(bad)
