@@ -84,17 +84,16 @@ def register_list_form(cfg):
 
 def one_pass_windows(cfg, cus=256):
     """Label windows of usl_backward's one-pass form (both products from one pass over g), or 0 where the library runs
-    the two separate products (its rule: windows of 15968 labels at most that send about 16 connections into a
-    feature, 16 * d / k >= 16384, whole blocks of 2048 features, enough workgroups to fill the chip, the partial sums
-    of the whole batch within 4 GiB)."""
+    the two separate products (its rule: windows of 8192 to 15968 labels that send about 16 connections into a
+    feature, whole blocks of 2048 features, enough workgroups to fill the chip)."""
     lists16 = 16 * cfg.d // cfg.k
-    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and lists16 == 16384):
+    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 8192 <= lists16 <= 16384):
         return 0
     cap = min(lists16, 15968) // 4 * 4
     nwin, nfb = -(-cfg.m // cap), cfg.d // 2048
     full = -(-nwin * nfb // cus) * cus // nfb
     nwin = full if nwin < full <= nwin * 5 // 4 else nwin
-    if nwin * nfb * 4 < cus * 3 or nwin * cfg.b * cfg.d * 4 > 1 << 32:
+    if nwin * nfb * 4 < cus * 3 or nwin * 64 * cfg.d * 4 > 1 << 32:
         return 0
     return nwin
 
@@ -102,8 +101,10 @@ def one_pass_windows(cfg, cus=256):
 def launches_in_call(cfg, call):
     """Kernel launches behind one call (the HIP-event time of the call covers all of them)."""
     if call == "backward":
-        if one_pass_windows(cfg):
-            return 3 + 3
+        nwin = one_pass_windows(cfg)
+        if nwin:
+            rows = max(64, min(cfg.b, (1 << 32) // (nwin * cfg.d * 4))) & ~1
+            return 3 + 2 * -(-cfg.b // rows) + 1
         return launches_in_call(cfg, "backward_weight") + launches_in_call(cfg, "backward_input")
     if call != "backward_input":
         return 2 if call == "bce" else 1

@@ -739,7 +739,7 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
            const uint16_t* __restrict__ feat, const uint32_t* __restrict__ caps, const uint32_t* __restrict__ ov_base,
            const OvEntry* __restrict__ ov, const uint32_t* __restrict__ ovr, float* __restrict__ partial,
            const uint32_t* __restrict__ rk, const uint32_t* __restrict__ ovrk, const uint32_t* __restrict__ ent_base,
-           float* __restrict__ stage, float* __restrict__ ovgw, const uint32_t* __restrict__ gate) {
+           float* __restrict__ stage, float* __restrict__ ovgw, const uint32_t* __restrict__ gate, int accumulate) {
     constexpr int KT = KT_BOTH;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     if (gate && *gate == 0) return;   // the kernels over the nonzero gradients do this call's work
@@ -953,7 +953,8 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
             if (r < CH) perm[r] = q < (uint32_t)NEAR2 ? ov_sum[q] : ovgw[(size_t)ov0 + q];
         }
         __syncthreads();
-        for (uint32_t r = threadIdx.x; r < min(CH, n_ent - c0); r += NT) stage[(size_t)e0 + c0 + r] = perm[r];
+        for (uint32_t r = threadIdx.x; r < min(CH, n_ent - c0); r += NT)   // a later pass over the batch adds to the earlier ones
+            stage[(size_t)e0 + c0 + r] = accumulate ? stage[(size_t)e0 + c0 + r] + perm[r] : perm[r];
     }
 }
 
@@ -1027,21 +1028,22 @@ bool usl_bwi_lds_applies(const usl_ctx* c) {
 }
 
 // ... and one for the kernel that computes both backward products from one pass of gathers?  The same with lists of
-// about 16 entries from windows of 16384 labels (k / d = 1/1024 at most: twice the windows, twice the partial sums).
+// about 16 entries from windows of 8192 to 16384 labels (k / d between 1/1024 and 1/512: twice the windows, twice the
+// partial sums).
 // USL_TUNE_BOTH=on forces it where the shape allows at all, =off forbids it.
-static bool lf_one_pass_fits(const usl_ctx* c);
+static bool lf_a_pass_fits(const usl_ctx* c);
 bool usl_both_lds_applies(const usl_ctx* c) {
-    if (!lf_shape_ok(c, 1) || !lf_one_pass_fits(c)) return false;
+    if (!lf_shape_ok(c, 1) || !lf_a_pass_fits(c)) return false;
     if (const char* e = getenv("USL_TUNE_BOTH")) {
         if (!strcmp(e, "on")) return true;
         if (!strcmp(e, "off")) return false;
     }
-    return (int64_t)16 * c->d / c->k >= 16384 && (int64_t)lf_windows(c, 1) * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
+    return (int64_t)16 * c->d / c->k >= 8192 && (int64_t)lf_windows(c, 1) * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
 }
 
-// The weight gradient is summed over the whole batch in registers: one pass, whose partial sums must fit 4 GiB.
-static bool lf_one_pass_fits(const usl_ctx* c) {
-    return (size_t)lf_windows(c, 1) * (size_t)c->max_b * (size_t)c->d * 4 <= ((size_t)1 << 32);
+// The partial sums of a pass of 64 instances (the fewest a pass takes) must fit 4 GiB.
+static bool lf_a_pass_fits(const usl_ctx* c) {
+    return (size_t)lf_windows(c, 1) * 64 * (size_t)c->d * 4 <= ((size_t)1 << 32);
 }
 
 template <int KT>
@@ -1126,12 +1128,12 @@ static usl_status lf_run_t(usl_ctx* c, int set, const float* g, const void* x, c
     const int nwin = lf_windows(c, set), wl = lf_window_labels(c, set), nfb = c->d / NF;
     // instances per pass: every pass loads the lists and the weights anew, and its partial sums are nwin * G * d
     // floats; as many as 4 GiB of partial sums allow, sized once for max_b.  The weight gradient is a sum over the
-    // whole batch, kept in registers: one pass there.
+    // whole batch, kept in registers during a pass: a later pass adds its sums to what the earlier ones left.
     int G = (int)(((size_t)1 << 32) / ((size_t)nwin * c->d * 4));
     if (const char* e = getenv("USL_TUNE_BWI_ROWS")) G = atoi(e) < G ? atoi(e) : G;   // tests: several passes on a small layer
     G = G < 64 ? 64 : G;
     G = G > c->max_b ? c->max_b : G;
-    if (BOTH) G = c->max_b;
+    if (BOTH && G > 1) G &= ~1;   // two instances per pass of the loop: an even number, so that only the last pass over the batch has an odd one left
     USL_TRY(usl_reserve(c, (void**)&L.partial, &L.partial_cap, (size_t)nwin * G * c->d * 4));
     const size_t lds = BOTH ? LDS2_BYTES : LDS_BYTES, N = (size_t)c->m * c->k;
     const unsigned grid = (unsigned)(((nwin + 7) / 8) * 8 * nfb);
@@ -1158,12 +1160,12 @@ static usl_status lf_run_t(usl_ctx* c, int set, const float* g, const void* x, c
                 USL_LDS_FORM(float, 0, k_both_lds, (const float*)x + (size_t)i0 * c->d, c->m, c->k, rows, c->d, wl, nfb, nwin, L.lab,
                              L.slot, L.feat, L.caps, L.ov_base, reinterpret_cast<const OvEntry*>(L.ov), L.ovr, L.partial, L.pos + N,
                              L.pos + N + (size_t)nwin * nfb * KT * NT, L.ov_base + 2 * ((size_t)nwin * nfb) + 1, L.stage,
-                             L.stage + N, gate);
+                             L.stage + N, gate, i0 > 0 ? 1 : 0);
             else
                 USL_LDS_FORM(uint16_t, 1, k_both_lds, (const uint16_t*)x + (size_t)i0 * c->d, c->m, c->k, rows, c->d, wl, nfb, nwin,
                              L.lab, L.slot, L.feat, L.caps, L.ov_base, reinterpret_cast<const OvEntry*>(L.ov), L.ovr, L.partial,
                              L.pos + N, L.pos + N + (size_t)nwin * nfb * KT * NT, L.ov_base + 2 * ((size_t)nwin * nfb) + 1,
-                             L.stage, L.stage + N, gate);
+                             L.stage, L.stage + N, gate, i0 > 0 ? 1 : 0);
         } else {
             if (c->storage == USL_F32)
                 USL_LDS_FORM(float, 0, k_bwi_lds, c->m, c->k, rows, c->d, wl, nfb, nwin, L.lab, L.slot, L.feat, L.caps, L.ov_base,

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 # (m, d, k, b, storage)
 SHAPES = [
-    (70000, 2048, 2, 5, "f32"),       # five windows of 14000 labels, an odd batch (the last pass has one instance)
+    (70000, 2048, 2, 5, "f32"),       # five windows of 14000 labels, an odd batch: a pass of four instances, then one of one
     (40000, 32768, 32, 3, "f32"),     # the headline's d and k
     (40000, 32768, 32, 4, "bf16"),
     (100000, 8192, 8, 37, "f32"),     # four feature blocks
@@ -22,6 +22,8 @@ SHAPES = [
     (99996, 4096, 6, 3, "bf16"),      # a window size that is no power of two, k no power of two
     (66000, 65536, 64, 2, "bf16"),    # d of two histogram chunks
     (65540, 6144, 12, 6, "f32"),      # three feature blocks, a last window with a ragged end
+    (70000, 2048, 2, 301, "f32"),     # three passes over the batch (128 + 128 + 45 instances: USL_TUNE_BWI_ROWS below), the weight
+                                      # gradient of a later pass added to the earlier ones
 ]
 
 
@@ -51,6 +53,7 @@ def test_backward_both_products(orc, m, d, k, b, storage, both, monkeypatch):
     import gpu_util as gu
     from paper_2306_03725_amd import usl
     monkeypatch.setenv("USL_TUNE_BOTH", both)
+    monkeypatch.setenv("USL_TUNE_BWI_ROWS", "128")
     cfg = wl.custom(m, d, k, b, storage=storage, positives=3, index=300 + SHAPES.index((m, d, k, b, storage)))
     print("backward", m, d, k, b, storage, both, flush=True)
     idx, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
