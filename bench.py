@@ -24,9 +24,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward": 3905316454, "backward_input": 2843423539, "forward": 924948889, "backward_weight": 940782387},
-    "large_wide": {"backward": 11245348454, "backward_input": 8593290035, "forward": 2478309376, "backward_weight": 2652058419},
-    "stress": {"backward": 230453621555, "backward_input": 204321744486, "forward": 26036561510, "backward_weight": 26131877068},
+    "large": {"backward": 3906574745, "backward_input": 2843213824, "forward": 924948889, "backward_weight": 940677529},
+    "large_wide": {"backward": 18212297113, "backward_input": 8594024038, "forward": 2478204518, "backward_weight": 2651429273},
+    "stress": {"backward": 229926607257, "backward_input": 203794730188, "forward": 26036666368, "backward_weight": 26131877068},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",

@@ -795,7 +795,7 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
         reinterpret_cast<uint32_t*>(lds_raw)[ZERO_LABEL2 + (threadIdx.x >> 5) * (RS2 / 4) + (threadIdx.x & 31)] = 0u;
     for (uint32_t q = NEAR2 + threadIdx.x; q < ov_n; q += NT) ovgw[(size_t)ov0 + q] = 0.f;   // entry q is lane q % NT's
     const int nl = (int)min((int64_t)wl, m - (int64_t)w * wl);   // labels of this window (the last one may be short)
-    const int nv = nl / 4, full = nv & ~63;                      // 16-byte pieces of a row slice; those in whole 1 KiB runs
+    const int nv = nl / 4;                                       // 16-byte pieces of a row slice
     const int lines = (nl * 4 + 127) / 128, per = (lines + nfb - 1) / nfb;   // 128-byte lines; this workgroup's share of the warm-up
     constexpr int XL = NF * (int)sizeof(TS) / 128;   // 128-byte lines of a feature block's activations
     // the rest of a list (r = start | n << 16 in ov_near, n even), two entries in flight at a time
@@ -839,17 +839,17 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(xrow + (size_t)(wv / PR) * d) + ((uint32_t)(wv % PR) * 1024u + (tid & 63u) * 16u)),
                                                  (__attribute__((address_space(3))) void*)(reinterpret_cast<unsigned char*>(outbuf) + (size_t)(wv / PR) * NF * sizeof(TS) + (size_t)(wv % PR) * 1024), 16, 0, 0);
         }
-        {   // the two row slices: whole 1 KiB pieces by LDS-DMA, the ragged end through registers
-            for (int v = (int)(tid >> 6) * 64; v < full; v += NT) {
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + ((uint32_t)v * 16u + (tid & 63u) * 16u)),
-                                                 (__attribute__((address_space(3))) void*)(lds_raw + (size_t)v * 16), 16, 0, 0);
-                if (pair)
-                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + (size_t)m * 4 + ((uint32_t)v * 16u + (tid & 63u) * 16u)),
-                                                     (__attribute__((address_space(3))) void*)(lds_raw + RS2 + (size_t)v * 16), 16, 0, 0);
-            }
-            for (int v = full + (int)tid; v < nv; v += NT) {
-                reinterpret_cast<uint4*>(lds_raw)[v] = reinterpret_cast<const uint4*>(grow)[v];
-                if (pair) reinterpret_cast<uint4*>(lds_raw + RS2)[v] = reinterpret_cast<const uint4*>(grow + (size_t)m * 4)[v];
+        {   // the two row slices by LDS-DMA, 1 KiB per wavefront and instruction; in the last piece only the lanes that
+            // still have 16 bytes of the slice take part (a lane's data lands at its own place whoever else is masked).
+            // Through registers, the ragged end cost a round trip to L2 per slice, one after the other.
+            for (int v = (int)(tid >> 6) * 64; v < nv; v += NT) {
+                if (v + (int)(tid & 63u) < nv) {
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + ((uint32_t)v * 16u + (tid & 63u) * 16u)),
+                                                     (__attribute__((address_space(3))) void*)(lds_raw + (size_t)v * 16), 16, 0, 0);
+                    if (pair)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow + (size_t)m * 4 + ((uint32_t)v * 16u + (tid & 63u) * 16u)),
+                                                         (__attribute__((address_space(3))) void*)(lds_raw + RS2 + (size_t)v * 16), 16, 0, 0);
+                }
             }
             if (!pair)   // an odd batch: the last pass has one instance, the second buffer reads as zeros
                 for (int v = (int)tid; v < nv; v += NT) reinterpret_cast<uint4*>(lds_raw + RS2)[v] = make_uint4(0u, 0u, 0u, 0u);
@@ -869,10 +869,12 @@ k_both_lds(const float* __restrict__ g, const TS* __restrict__ W, const TS* __re
         }
         if (i + 2 < rows) {   // one load per 128-byte line of what the next pass reads: the window's workgroups share
             // the lines of its two slices of g, then come the block's own lines of the two rows of x
-            for (int j = (int)tid; j < 2 * per + 2 * XL; j += NT) {
-                const int r = j < 2 * per ? j / per : (j - 2 * per) / XL, c = j < 2 * per ? fb * per + j % per : (j - 2 * per) % XL;
-                const char* line = (j < 2 * per ? grow + (size_t)m * 4 * (2 + r) : reinterpret_cast<const char*>(xrow + (size_t)(2 + r) * d)) + (size_t)c * 128;
-                if (i + 2 + r < rows && (j >= 2 * per || c < lines))
+            for (int j = (int)tid; j < 2 * per + 2 * XL; j += NT) {   // (no divisions: every lane comes through here)
+                const bool of_g = j < 2 * per;
+                const int jj = of_g ? j : j - 2 * per, half = of_g ? per : XL;
+                const int r = jj >= half ? 1 : 0, c = (of_g ? fb * per : 0) + jj - r * half;
+                const char* line = (of_g ? grow + (size_t)m * 4 * (2 + r) : reinterpret_cast<const char*>(xrow + (size_t)(2 + r) * d)) + (size_t)c * 128;
+                if (i + 2 + r < rows && (!of_g || c < lines))
                     asm volatile("global_load_dword %0, %1, off" : "+v"(token) : "v"(line));
             }
         }
