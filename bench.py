@@ -24,9 +24,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published peak
 # They are measured offline (a counter run serialises the kernels) and go stale when a kernel changes: the
 # profile files carry the date of truth, these constants only repeat their per-call totals.
 MEASURED_TRAFFIC_BYTES = {
-    "large": {"backward": 3906574745, "backward_input": 2843213824, "forward": 924948889, "backward_weight": 940677529},
-    "large_wide": {"backward": 18212297113, "backward_input": 8594024038, "forward": 2478204518, "backward_weight": 2651429273},
-    "stress": {"backward": 229926607257, "backward_input": 203794730188, "forward": 26036666368, "backward_weight": 26131877068},
+    "large": {"backward": 3903848448, "backward_input": 2844157542, "forward": 924948889, "backward_weight": 940782387},
+    "large_wide": {"backward": 17392939827, "backward_input": 8593394892, "forward": 2478204518, "backward_weight": 2651114700},
+    "stress": {"backward": 178784619724, "backward_input": 203820315443, "forward": 26037190656, "backward_weight": 26132296499},
 }
 KERNELS_OF_CALL = {
     "forward": "k_forward (1 launch)",
@@ -63,6 +63,9 @@ def algorithmic_bytes(cfg):
     return per
 
 
+PARTIAL_SUM_BYTES = 16 << 30   # what the library lets the partial sums of a pass over the batch take on this device
+
+
 def register_list_windows(cfg, cus=256):
     """Label windows of usl_backward_input's register-list form for this shape, or 0 where the library keeps the other
     form (its rule: windows of 16384 to 32768 labels that send about 32 connections into a feature, whole blocks of
@@ -84,16 +87,16 @@ def register_list_form(cfg):
 
 def one_pass_windows(cfg, cus=256):
     """Label windows of usl_backward's one-pass form (both products from one pass over g), or 0 where the library runs
-    the two separate products (its rule: windows of 8192 to 15968 labels that send about 16 connections into a
+    the two separate products (its rule: windows of 8192 to 15968 labels that send 16 connections or fewer into a
     feature, whole blocks of 2048 features, enough workgroups to fill the chip)."""
     lists16 = 16 * cfg.d // cfg.k
-    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 8192 <= lists16 <= 16384):
+    if not (cfg.d % 2048 == 0 and cfg.d <= 65536 and cfg.m % 4 == 0 and 8192 <= lists16 <= 32768):
         return 0
     cap = min(lists16, 15968) // 4 * 4
     nwin, nfb = -(-cfg.m // cap), cfg.d // 2048
     full = -(-nwin * nfb // cus) * cus // nfb
     nwin = full if nwin < full <= nwin * 5 // 4 else nwin
-    if nwin * nfb * 4 < cus * 3 or nwin * 64 * cfg.d * 4 > 1 << 32:
+    if nwin * nfb * 4 < cus * 3 or nwin * 64 * cfg.d * 4 > PARTIAL_SUM_BYTES:
         return 0
     return nwin
 
@@ -103,7 +106,7 @@ def launches_in_call(cfg, call):
     if call == "backward":
         nwin = one_pass_windows(cfg)
         if nwin:
-            rows = max(64, min(cfg.b, (1 << 32) // (nwin * cfg.d * 4))) & ~1
+            rows = max(64, min(cfg.b, PARTIAL_SUM_BYTES // (nwin * cfg.d * 4))) & ~1
             return 3 + 2 * -(-cfg.b // rows) + 1
         return launches_in_call(cfg, "backward_weight") + launches_in_call(cfg, "backward_input")
     if call != "backward_input":
@@ -111,7 +114,7 @@ def launches_in_call(cfg, call):
     groups = -(-cfg.b // 256)
     nwin = register_list_windows(cfg)
     if nwin:
-        passes = -(-cfg.b // max(64, min(cfg.b, (1 << 32) // (nwin * cfg.d * 4))))
+        passes = -(-cfg.b // max(64, min(cfg.b, PARTIAL_SUM_BYTES // (nwin * cfg.d * 4))))
         return 3 + passes * 2
     win = int((24576.0 * ((cfg.d / 32768.0) * (32.0 / cfg.k)) ** 0.5 + 2048.0) / 4096.0) * 4096   # labels per window,
     win = min(max(win, 16384), 49152)                                                              # as the library picks them

@@ -1007,12 +1007,25 @@ static int lf_window_labels(const usl_ctx* c, int set) {
     return (int)(((c->m + nwin - 1) / nwin + 3) / 4 * 4);
 }
 
+// The most that the partial sums of a pass over the batch may take: 16 GiB on a device with 128 GiB or more (every
+// pass loads lists and weights anew: at m = 3M, d = 65536, b = 1024 the two products take 74 ms with passes of 4 GiB,
+// 62 ms with passes of 16 GiB, 65 ms with one pass of 48 GiB), else 4 GiB.  USL_TUNE_LF_GIB overrides.
+static size_t lf_partial_bytes() {
+    if (const char* e = getenv("USL_TUNE_LF_GIB")) return (size_t)(atoi(e) > 0 ? atoi(e) : 1) << 30;
+    static size_t cached = 0;
+    if (!cached) {
+        size_t free_b = 0, total_b = 0;
+        cached = (hipMemGetInfo(&free_b, &total_b) == hipSuccess && total_b >= ((size_t)128 << 30)) ? (size_t)16 << 30 : (size_t)4 << 30;
+    }
+    return cached;
+}
+
 // runs of SEG slots in a window of the lists for both products
 static int lf_runs(const usl_ctx* c) { return (int)(((int64_t)lf_window_labels(c, 1) * c->k + SEG - 1) / SEG); }
 
 static bool lf_shape_ok(const usl_ctx* c, int set) {
     const int64_t lists = (int64_t)(set ? 16 : 32) * c->d / c->k;   // labels that send that many connections into a feature
-    return c->d % NF == 0 && c->d <= 65536 && c->m % 4 == 0 && lists >= 2048 && lists <= (set ? WL / 2 : WL) &&
+    return c->d % NF == 0 && c->d <= 65536 && c->m % 4 == 0 && lists >= 2048 && lists <= WL &&
            c->m * (int64_t)c->k < (int64_t)PAD_SLOT;
 }
 
@@ -1030,7 +1043,7 @@ bool usl_bwi_lds_applies(const usl_ctx* c) {
 }
 
 // ... and one for the kernel that computes both backward products from one pass of gathers?  The same with lists of
-// about 16 entries from windows of 8192 to 16384 labels (k / d between 1/1024 and 1/512: twice the windows, twice the
+// 16 entries or fewer from windows of 8192 to 15968 labels (k / d of 1/512 or less: twice the windows, twice the
 // partial sums).
 // USL_TUNE_BOTH=on forces it where the shape allows at all, =off forbids it.
 static bool lf_a_pass_fits(const usl_ctx* c);
@@ -1043,9 +1056,9 @@ bool usl_both_lds_applies(const usl_ctx* c) {
     return (int64_t)16 * c->d / c->k >= 8192 && (int64_t)lf_windows(c, 1) * (c->d / NF) * 4 >= (int64_t)c->num_cu * 3;
 }
 
-// The partial sums of a pass of 64 instances (the fewest a pass takes) must fit 4 GiB.
+// The partial sums of a pass of 64 instances (the fewest a pass takes) must fit the allowance.
 static bool lf_a_pass_fits(const usl_ctx* c) {
-    return (size_t)lf_windows(c, 1) * 64 * (size_t)c->d * 4 <= ((size_t)1 << 32);
+    return (size_t)lf_windows(c, 1) * 64 * (size_t)c->d * 4 <= lf_partial_bytes();
 }
 
 template <int KT>
@@ -1129,9 +1142,9 @@ static usl_status lf_run_t(usl_ctx* c, int set, const float* g, const void* x, c
     const uint32_t* stale = reinterpret_cast<const uint32_t*>(c->idx_print) + 4;
     const int nwin = lf_windows(c, set), wl = lf_window_labels(c, set), nfb = c->d / NF;
     // instances per pass: every pass loads the lists and the weights anew, and its partial sums are nwin * G * d
-    // floats; as many as 4 GiB of partial sums allow, sized once for max_b.  The weight gradient is a sum over the
+    // floats; as many as the allowance for partial sums admits, sized once for max_b.  The weight gradient is a sum over the
     // whole batch, kept in registers during a pass: a later pass adds its sums to what the earlier ones left.
-    int G = (int)(((size_t)1 << 32) / ((size_t)nwin * c->d * 4));
+    int G = (int)(lf_partial_bytes() / ((size_t)nwin * c->d * 4));
     if (const char* e = getenv("USL_TUNE_BWI_ROWS")) G = atoi(e) < G ? atoi(e) : G;   // tests: several passes on a small layer
     G = G < 64 ? 64 : G;
     G = G > c->max_b ? c->max_b : G;

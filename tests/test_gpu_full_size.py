@@ -96,6 +96,16 @@ def run_full(cfg, orc, full_loss, n_lab=4096, n_inst=4):
     assert_close(gW_J, orc.backward_weight(g_J, x, np.ascontiguousarray(idx[J])), 1e-5, "grad_W rows")
     assert_close(gu.host(gx.index_select(0, dI)), orc.backward_input(g_I, idx, W, d), 1e-4, "grad_x rows")
     print("backward ok", flush=True)
+    # ... and both from one call (usl_backward, the form bench.py times)
+    gW2, gx2 = gu.empty((m, k)).fill_(float("nan")), gu.empty((b, d)).fill_(float("nan"))
+    L.backward(out, d_x, d_idx, d_W, gW2, gx2, b)
+    assert_close(gu.host(gW2.index_select(0, dJ)), orc.backward_weight(g_J, x, np.ascontiguousarray(idx[J])), 1e-5, "grad_W rows, one call")
+    assert_close(gu.host(gx2.index_select(0, dI)), orc.backward_input(g_I, idx, W, d), 1e-4, "grad_x rows, one call")
+    # every element, against the separate calls (same sums in another order)
+    assert float((gW2 - gW).abs().max().item()) <= 1e-5 * float(gW.abs().max().item())
+    assert float((gx2 - gx).abs().max().item()) <= 1e-4 * float(gx.abs().max().item())
+    del gW2, gx2
+    print("backward in one call ok", flush=True)
     # Adam on sampled rows
     d_m1, d_m2 = gu.dev(np.zeros((m, k), np.float32)), gu.dev(np.zeros((m, k), np.float32))
     for t in (1, 2):
