@@ -74,7 +74,8 @@ usl_status usl_invalidate(usl_ctx* ctx);
  * address, or from a checkpoint copied into it.  As a safety net every usl_backward_input on an address it
  * already has lists for re-reads a sample of idx (64 KiB) on the device and compares its fingerprint with the
  * one taken when the lists were built; on a mismatch that call fills grad_x with NaN instead of numbers from
- * stale lists, and the condition stays recorded.  usl_check waits for the stream and returns USL_ESTALE if
+ * stale lists, and the condition stays recorded (usl_backward and usl_train_step, where they take the weight
+ * gradient from such lists too: grad_W becomes NaN as well, and usl_train_step leaves W, m1, m2 as they were).  usl_check waits for the stream and returns USL_ESTALE if
  * that happened since the last check (and invalidates the private views), USL_OK otherwise.  A change of a
  * single entry can escape the sample: usl_invalidate remains the contract, this is the net under it. */
 usl_status usl_check(usl_ctx* ctx);

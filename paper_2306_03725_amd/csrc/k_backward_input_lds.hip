@@ -1206,11 +1206,13 @@ usl_status usl_bwi_lds_run(usl_ctx* c, const float* g, const int32_t* idx, const
 
 // grad_x[b][d] and the weight gradient from g[b][m] and x[b][d].  The weight gradient is left in the order of the lists:
 // slot f's is (*stage)[(*pos)[f]] (usl_launch_adam_staged takes it from there); both arrays belong to the context and
-// hold until the next call or a change of idx.  A stale idx (see usl_check) poisons grad_x only.
+// hold until the next call or a change of idx.  A stale idx (see usl_check) poisons grad_x here; *stale is the device
+// word that says so, for whoever picks up the weight gradient.
 usl_status usl_both_lds_run(usl_ctx* c, const float* g, const void* x, const int32_t* idx, const void* W, float* grad_x,
-                            int32_t b, const uint32_t* gate, const float** stage, const uint32_t** pos) {
+                            int32_t b, const uint32_t* gate, const float** stage, const uint32_t** pos, const uint32_t** stale) {
     USL_TRY((lf_run_t<KT_BOTH, true>(c, 1, g, x, idx, W, grad_x, b, gate)));
     *stage = c->lf[1].stage;
     *pos = c->lf[1].pos;
+    *stale = reinterpret_cast<const uint32_t*>(c->idx_print) + 4;
     return USL_OK;
 }

@@ -273,14 +273,16 @@ k_adam(TS* __restrict__ W, const float* __restrict__ gW, float* __restrict__ m1,
 // usl_backward; usl_train_step lets Adam do it in passing).  Blocks and XCDs as in k_adam_staged.
 __global__ void __launch_bounds__(256)
 k_unstage(const float* __restrict__ stage, const uint32_t* __restrict__ pos, const uint32_t* __restrict__ gate,
-          float* __restrict__ gW, size_t n4) {
+          const uint32_t* __restrict__ stale, float* __restrict__ gW, size_t n4) {
     if (gate && *gate == 0) return;
+    const bool poison = *stale != 0;   // the lists were built from other contents of idx: no number is better than a wrong one
     const size_t per_xcd = (n4 + 7) / 8, first = (size_t)(blockIdx.x & 7) * per_xcd;
     const size_t last = first + per_xcd < n4 ? first + per_xcd : n4;
     const size_t stride = (size_t)(gridDim.x / 8) * 256;
     for (size_t v = first + (size_t)(blockIdx.x >> 3) * 256 + threadIdx.x; v < last; v += stride) {
         const uint4 p4 = reinterpret_cast<const uint4*>(pos)[v];
-        reinterpret_cast<float4*>(gW)[v] = make_float4(stage[p4.x], stage[p4.y], stage[p4.z], stage[p4.w]);
+        const float nan = __uint_as_float(0x7FC00000u);
+        reinterpret_cast<float4*>(gW)[v] = poison ? make_float4(nan, nan, nan, nan) : make_float4(stage[p4.x], stage[p4.y], stage[p4.z], stage[p4.w]);
     }
 }
 
@@ -290,12 +292,16 @@ k_unstage(const float* __restrict__ stage, const uint32_t* __restrict__ pos, con
 // eighth of the array, the eighth of its XCD (blocks are dealt to the 8 XCDs round robin): the part of stage that
 // the slots of a window point into (a few MiB) is then fetched by one L2 only and stays there while they are done.
 // gate (may be null): zero means the kernels over the listed nonzero gradients wrote grad_W themselves; read it.
+// stale: nonzero means the lists were built from other contents of idx (see usl_check); grad_W then becomes NaN and W,
+// m1, m2 stay as they are -- a step from a wrong gradient could not be taken back.
 template <typename TS>
 __global__ void __launch_bounds__(256)
 k_adam_staged(TS* __restrict__ W, const float* __restrict__ stage, const uint32_t* __restrict__ pos,
-              const uint32_t* __restrict__ gate, float* __restrict__ gW, float* __restrict__ m1, float* __restrict__ m2,
-              size_t n4, float lr, float b1, float b2, float eps, float ic1, float ic2) {
+              const uint32_t* __restrict__ gate, const uint32_t* __restrict__ stale, float* __restrict__ gW,
+              float* __restrict__ m1, float* __restrict__ m2, size_t n4, float lr, float b1, float b2, float eps, float ic1,
+              float ic2) {
     const bool listed = gate && *gate == 0;
+    const bool poison = !listed && *stale != 0;
     const size_t per_xcd = (n4 + 7) / 8, first = (size_t)(blockIdx.x & 7) * per_xcd;
     const size_t last = first + per_xcd < n4 ? first + per_xcd : n4;
     const size_t stride = (size_t)(gridDim.x / 8) * 256;
@@ -306,6 +312,11 @@ k_adam_staged(TS* __restrict__ W, const float* __restrict__ stage, const uint32_
             g4 = *reinterpret_cast<const float4*>(gW + f);
         } else {
             const uint4 p4 = *reinterpret_cast<const uint4*>(pos + f);
+            if (poison) {
+                const float nan = __uint_as_float(0x7FC00000u);
+                *reinterpret_cast<float4*>(gW + f) = make_float4(nan, nan, nan, nan);
+                continue;
+            }
             g4 = make_float4(stage[p4.x], stage[p4.y], stage[p4.z], stage[p4.w]);
             *reinterpret_cast<float4*>(gW + f) = g4;
         }
@@ -449,18 +460,19 @@ usl_status usl_launch_adam(usl_ctx* c, void* W, const float* grad_W, float* m1, 
     return usl_check_launch(c, "adam");
 }
 
-usl_status usl_launch_unstage(usl_ctx* c, const float* stage, const uint32_t* pos, const uint32_t* gate, float* grad_W) {
+usl_status usl_launch_unstage(usl_ctx* c, const float* stage, const uint32_t* pos, const uint32_t* gate, const uint32_t* stale,
+                              float* grad_W) {
     const size_t n = (size_t)c->m * c->k;
     if ((uintptr_t)grad_W % 16 || n % 4) USL_FAIL(c, USL_EINVAL, "grad_W must be 16-byte aligned, m * k a multiple of 4");
     const unsigned blocks = (unsigned)(c->num_cu > 0 ? c->num_cu : 8) * 16 / 8 * 8;
-    hipLaunchKernelGGL(k_unstage, dim3(blocks), dim3(256), 0, c->stream, stage, pos, gate, grad_W, n / 4);
+    hipLaunchKernelGGL(k_unstage, dim3(blocks), dim3(256), 0, c->stream, stage, pos, gate, stale, grad_W, n / 4);
     return usl_check_launch(c, "weight gradient into slot order");
 }
 
 // Adam from a weight gradient in list order (see k_adam_staged); m * k must be a multiple of 4 (the list form's
 // shapes are).  grad_W is written (or, behind a zero gate, read).
 usl_status usl_launch_adam_staged(usl_ctx* c, void* W, const float* stage, const uint32_t* pos, const uint32_t* gate,
-                                  float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
+                                  const uint32_t* stale, float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
                                   float inv_c1, float inv_c2) {
     const size_t n = (size_t)c->m * c->k;
     const bool aligned = ((uintptr_t)W % 16 == 0) && ((uintptr_t)grad_W % 16 == 0) &&
@@ -469,10 +481,10 @@ usl_status usl_launch_adam_staged(usl_ctx* c, void* W, const float* stage, const
     const unsigned blocks = (unsigned)(c->num_cu > 0 ? c->num_cu : 8) * 16 / 8 * 8;
     if (c->storage == USL_F32)
         hipLaunchKernelGGL(k_adam_staged<float>, dim3(blocks), dim3(256), 0, c->stream, (float*)W, stage, pos, gate,
-                           grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
+                           stale, grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
     else
         hipLaunchKernelGGL(k_adam_staged<uint16_t>, dim3(blocks), dim3(256), 0, c->stream, (uint16_t*)W, stage, pos, gate,
-                           grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
+                           stale, grad_W, m1, m2, n / 4, lr, beta1, beta2, eps, inv_c1, inv_c2);
     return usl_check_launch(c, "adam (staged gradient)");
 }
 

@@ -282,7 +282,7 @@ static usl_status subset_context(usl_ctx* c, int64_t n, const int32_t* idx, cons
 // usl_train_step); the kernels over the lists and the dense ones stand on either side of the gate.
 static usl_status backward_both(usl_ctx* c, const float* g, const void* x, const int32_t* idx, const void* W, float* grad_W,
                                 float* grad_x, int32_t b, bool lists, bool dense, const uint32_t** gate_out,
-                                const float** stage, const uint32_t** pos) {
+                                const float** stage, const uint32_t** pos, const uint32_t** stale) {
     const uint32_t* gate = nullptr;
     if (lists) USL_TRY(usl_sparse_compact(c, g, b, &gate));
     c->nz_lists_of = g;
@@ -295,7 +295,7 @@ static usl_status backward_both(usl_ctx* c, const float* g, const void* x, const
         // the two dense kernels it stands for.  The weight gradient is left in the order of the lists.
         if (gate) s = usl_sparse_backward_weight(c, x, idx, grad_W, b);
         if (gate && s == USL_OK) s = usl_sparse_backward_input(c, idx, W, grad_x, b);
-        if (s == USL_OK) s = usl_both_lds_run(c, g, x, idx, W, grad_x, b, gate, stage, pos);
+        if (s == USL_OK) s = usl_both_lds_run(c, g, x, idx, W, grad_x, b, gate, stage, pos, stale);
     } else {
         s = usl_launch_backward_weight(c, g, x, idx, grad_W, b, dense);
         if (s == USL_OK) s = usl_launch_backward_input(c, g, idx, W, grad_x, b);
@@ -314,8 +314,9 @@ extern "C" usl_status usl_backward(usl_ctx* c, const float* g, const void* x, co
     const uint32_t* gate = nullptr;
     const float* stage = nullptr;
     const uint32_t* pos = nullptr;
-    USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, usl_sparse_supported(c), false, &gate, &stage, &pos));
-    if (stage) USL_TRY(usl_launch_unstage(c, stage, pos, gate, grad_W));
+    const uint32_t* stale = nullptr;
+    USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, usl_sparse_supported(c), false, &gate, &stage, &pos, &stale));
+    if (stage) USL_TRY(usl_launch_unstage(c, stage, pos, gate, stale, grad_W));
     return USL_OK;
 }
 
@@ -403,11 +404,12 @@ extern "C" usl_status usl_train_step(usl_ctx* c, const void* x, const int32_t* i
             const uint32_t* gate = nullptr;
             const float* stage = nullptr;
             const uint32_t* pos = nullptr;
-            USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, lists, loss_kind == 0, &gate, &stage, &pos));
+            const uint32_t* stale = nullptr;
+            USL_TRY(backward_both(c, g, x, idx, W, grad_W, grad_x, b, lists, loss_kind == 0, &gate, &stage, &pos, &stale));
             if (stage) {   // the weight gradient is in the order of the lists: Adam picks it up there and writes grad_W
                 const double c1 = 1.0 - pow((double)beta1, (double)t);
                 const double c2 = 1.0 - pow((double)beta2, (double)t);
-                return usl_launch_adam_staged(c, W, stage, pos, gate, grad_W, m1, m2, lr, beta1, beta2, eps, (float)(1.0 / c1),
+                return usl_launch_adam_staged(c, W, stage, pos, gate, stale, grad_W, m1, m2, lr, beta1, beta2, eps, (float)(1.0 / c1),
                                               (float)(1.0 / c2));
             }
         } else {

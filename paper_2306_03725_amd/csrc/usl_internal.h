@@ -142,11 +142,12 @@ usl_status usl_bwi_lds_run(usl_ctx* ctx, const float* g, const int32_t* idx, con
 // grad_W[m][k] and grad_x[b][d] from g[b][m] and x[b][d]; for layers with k / d <= 1/1024, one pass over the batch.
 bool usl_both_lds_applies(const usl_ctx* ctx);
 usl_status usl_both_lds_run(usl_ctx* ctx, const float* g, const void* x, const int32_t* idx, const void* W, float* grad_x,
-                            int32_t b, const uint32_t* gate, const float** stage, const uint32_t** pos);
+                            int32_t b, const uint32_t* gate, const float** stage, const uint32_t** pos, const uint32_t** stale);
 // grad_W[f] = stage[pos[f]] (behind a zero gate: nothing, the kernels over the listed nonzeros wrote grad_W)
-usl_status usl_launch_unstage(usl_ctx* ctx, const float* stage, const uint32_t* pos, const uint32_t* gate, float* grad_W);
+usl_status usl_launch_unstage(usl_ctx* ctx, const float* stage, const uint32_t* pos, const uint32_t* gate, const uint32_t* stale,
+                              float* grad_W);
 usl_status usl_launch_adam_staged(usl_ctx* ctx, void* W, const float* stage, const uint32_t* pos, const uint32_t* gate,
-                                  float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
+                                  const uint32_t* stale, float* grad_W, float* m1, float* m2, float lr, float beta1, float beta2, float eps,
                                   float inv_c1, float inv_c2);
 // Records (store = 1) the fingerprint of idx in ctx->idx_print, or compares with the recorded one (store = 0) and
 // raises the stale word (32-bit word 4 of idx_print) on a difference.

@@ -113,3 +113,50 @@ def test_backward_of_a_gradient_that_is_almost_all_zeros(orc, monkeypatch):
     assert_close(gu.host(gx), orc.backward_input(g2, idx, W, d), 1e-4, "grad_x, dense again")
     L.check()
     L.close()
+
+
+def test_changed_idx_is_noticed_before_the_weights_move(orc, monkeypatch):
+    """Contents of idx replaced at the same address without usl_invalidate (past the binding, which would notice): the
+    lists of the one-pass form are stale.  Both gradients come back as NaN, usl_train_step leaves W, m1 and m2 as they
+    were (a step from a wrong gradient could not be taken back), usl_check says USL_ESTALE; the next call is right."""
+    import torch
+    import gpu_util as gu
+    from paper_2306_03725_amd import usl
+    monkeypatch.setenv("USL_TUNE_BOTH", "on")
+    m, d, k, b = 70000, 2048, 2, 4
+    cfg = wl.custom(m, d, k, b, positives=3, index=350)
+    hp = wl.ADAM
+    idx1, W, x, g = wl.gen_idx(cfg), wl.gen_W(cfg), wl.gen_x(cfg), wl.gen_g(cfg)
+    idx2 = wl.gen_idx(wl.custom(m, d, k, b, index=351))
+    off, lab = wl.gen_targets(cfg)
+    L = usl.Layer(m, d, k, b)
+    d_idx, d_W, d_x, d_g = gu.dev(idx1), gu.dev(W), gu.dev(x), gu.dev(g)
+    gW, gx = gu.empty((m, k)), gu.empty((b, d))
+    p = lambda t: t.data_ptr()
+    L.backward(d_g, d_x, d_idx, d_W, gW, gx, b)
+    assert_close(gu.host(gW), orc.backward_weight(g, x, idx1), 1e-5, "grad_W, first idx")
+    d_idx.copy_(torch.from_numpy(idx2))
+    assert usl._lib.usl_backward(L._h, p(d_g), p(d_x), p(d_idx), p(d_W), p(gW), p(gx), b) == usl.USL_OK
+    assert torch.isnan(gW).all() and torch.isnan(gx).all()
+    # the whole step on the stale lists
+    d_m1, d_m2 = gu.dev(np.zeros((m, k), np.float32)), gu.dev(np.zeros((m, k), np.float32))
+    d_off, d_lab, loss, out = gu.dev(off), gu.dev(lab), gu.empty((1,)), gu.empty((b, m))
+    gW.zero_(); gx.zero_()
+    scale = float(np.float32(1.0 / b))
+    step = lambda: usl._lib.usl_train_step(L._h, p(d_x), p(d_idx), p(d_W), p(d_m1), p(d_m2), p(d_off), p(d_lab), 0, scale, 1,
+                                           hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], p(out), p(gW), p(gx), p(loss), b)
+    assert step() == usl.USL_OK
+    assert torch.isnan(gW).all() and torch.isnan(gx).all()
+    np.testing.assert_array_equal(gu.host(d_W), W)
+    assert not gu.host(d_m1).any() and not gu.host(d_m2).any()
+    with pytest.raises(usl.UslError) as e:
+        L.check()
+    assert e.value.status == usl.USL_ESTALE
+    # the check invalidated the lists: the same call is right now
+    assert step() == usl.USL_OK
+    got_g = gu.host(out)
+    assert_close(gu.host(gW), orc.backward_weight(got_g, x, idx2), 1e-5, "grad_W after the check")
+    assert_close(gu.host(gx), orc.backward_input(got_g, idx2, W, d), 1e-4, "grad_x after the check")
+    assert (gu.host(d_W) != W).any()
+    L.check()
+    L.close()
