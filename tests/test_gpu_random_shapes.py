@@ -52,7 +52,13 @@ def test_random_shape(orc, m, d, k, b, storage):
     L.backward_input(d_g, d_idx, d_W, gx, b)
     assert_close(gu.host(out), orc.forward(x, idx, W), 1e-5, "out")
     assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W")
-    assert_close(gu.host(gx), orc.backward_input(g, idx, W, d), 1e-4, "grad_x")
+    ref_gx = orc.backward_input(g, idx, W, d)
+    assert_close(gu.host(gx), ref_gx, 1e-4, "grad_x")
+    # both backward products from one call
+    gW.fill_(float("nan")); gx.fill_(float("nan"))
+    L.backward(d_g, d_x, d_idx, d_W, gW, gx, b)
+    assert_close(gu.host(gW), orc.backward_weight(g, x, idx), 1e-5, "grad_W (one call)")
+    assert_close(gu.host(gx), ref_gx, 1e-4, "grad_x (one call)")
     # redistribution of a third of the layer, then the fused step on the new connectivity
     r = wl.rng(cfg, 4)
     m1 = (r.standard_normal((m, k)) * 1e-3).astype(np.float32)
